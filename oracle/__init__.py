@@ -1,0 +1,14 @@
+"""fp64 CPU oracle (test infrastructure, not the product).
+
+Only tests, `__graft_entry__.smoke()` and `bench.py`'s cpu_baseline leg may import
+this package. It never imports the HIP package and shares no code with it.
+"""
+from .tf_oracle import (  # noqa: F401
+    accept,
+    attention,
+    build_oracle,
+    chunk_mean,
+    gather,
+    num_threads,
+    retrieve,
+)

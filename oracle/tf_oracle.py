@@ -1,0 +1,146 @@
+"""ctypes front end of the plain-C fp64 oracle (`tf_oracle.c`).
+
+TEST INFRASTRUCTURE: argument marshalling only; every number comes from the C file.
+Arrays are numpy: bf16 tensors travel as uint16 bit patterns, results are float64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tf_oracle.c")
+_LIB = os.path.join(_HERE, "libtf_oracle.so")
+_lib = None
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile tf_oracle.c with gcc (-O2, no fast-math, OpenMP). Returns the .so path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build_oracle())
+        _lib.orc_num_threads.restype = ctypes.c_int
+        for name in ("orc_attention", "orc_chunk_mean", "orc_retrieve", "orc_gather", "orc_accept"):
+            getattr(_lib, name).restype = ctypes.c_int
+    return _lib
+
+
+def _p(a: np.ndarray, typ):
+    return a.ctypes.data_as(typ)
+
+
+def _u16(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def attention(Q, K, V, kv_len=None, scale: float = 1.0, causal: bool = True):
+    """Q [B,H,G,d], K,V [B,H,N,d] uint16(bf16) -> (O f64 [B,H,G,d], LSE f64 [B,H,G], wsum f64 [B,H,G])."""
+    Q, K, V = _u16(Q), _u16(K), _u16(V)
+    B, H, G, d = Q.shape
+    N = K.shape[2]
+    assert K.shape == (B, H, N, d) and V.shape == K.shape
+    if kv_len is None:
+        kv = np.full(B, N, dtype=np.int32)
+    else:
+        kv = np.ascontiguousarray(np.broadcast_to(np.asarray(kv_len, dtype=np.int32), (B,)))
+    O = np.empty((B, H, G, d), dtype=np.float64)
+    LSE = np.empty((B, H, G), dtype=np.float64)
+    ws = np.empty((B, H, G), dtype=np.float64)
+    rc = _load().orc_attention(_p(Q, _u16p), _p(K, _u16p), _p(V, _u16p), B, H, G,
+                               ctypes.c_int64(N), d, _p(kv, _i32p), ctypes.c_double(scale),
+                               int(bool(causal)), _p(O, _f64p), _p(LSE, _f64p), _p(ws, _f64p))
+    if rc != 0:
+        raise ValueError("orc_attention: bad argument")
+    return O, LSE, ws
+
+
+def chunk_mean(K, c: int) -> np.ndarray:
+    """K [B,H,N,d] uint16(bf16) -> Kmean f64 [B,H,N//c,d]."""
+    K = _u16(K)
+    B, H, N, d = K.shape
+    M = N // c
+    out = np.empty((B, H, M, d), dtype=np.float64)
+    rc = _load().orc_chunk_mean(_p(K, _u16p), B, H, ctypes.c_int64(N), d, int(c), _p(out, _f64p))
+    if rc != 0:
+        raise ValueError("orc_chunk_mean: bad argument")
+    return out
+
+
+def retrieve(q_r, Kmean, k: int, n_chunks=None):
+    """q_r [B,H,d] uint16(bf16), Kmean f64 [B,H,M,d] -> (scores f64 [B,H,M], idx int32 [B,H,k])."""
+    q_r = _u16(q_r)
+    Kmean = np.ascontiguousarray(Kmean, dtype=np.float64)
+    B, H, M, d = Kmean.shape
+    assert q_r.shape == (B, H, d)
+    if n_chunks is None:
+        nc = np.full(B, M, dtype=np.int32)
+    else:
+        nc = np.ascontiguousarray(np.broadcast_to(np.asarray(n_chunks, dtype=np.int32), (B,)))
+    scores = np.empty((B, H, M), dtype=np.float64)
+    idx = np.empty((B, H, k), dtype=np.int32)
+    rc = _load().orc_retrieve(_p(q_r, _u16p), _p(Kmean, _f64p), B, H, ctypes.c_int64(M), d,
+                              _p(nc, _i32p), int(k), _p(scores, _f64p), _p(idx, _i32p))
+    if rc != 0:
+        raise ValueError("orc_retrieve: bad argument")
+    return scores, idx
+
+
+def gather(K, V, idx, c: int, R_cap: int | None = None):
+    """K,V [B,H,N,d] uint16, idx int32 [B,H,k] -> (Kr, Vr) uint16 [B,H,R_cap,d]; rows >= k*c are zero."""
+    K, V = _u16(K), _u16(V)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    B, H, N, d = K.shape
+    k = idx.shape[2]
+    R_cap = k * c if R_cap is None else int(R_cap)
+    Kr = np.zeros((B, H, R_cap, d), dtype=np.uint16)
+    Vr = np.zeros((B, H, R_cap, d), dtype=np.uint16)
+    rc = _load().orc_gather(_p(K, _u16p), _p(V, _u16p), B, H, ctypes.c_int64(N), d, int(c),
+                            _p(idx, _i32p), k, ctypes.c_int64(R_cap), _p(Kr, _u16p), _p(Vr, _u16p))
+    if rc != 0:
+        raise ValueError("orc_gather: bad argument")
+    return Kr, Vr
+
+
+def accept(target_logits, draft_logits, draft_tokens, temperature: float, u_accept, u_sample):
+    """-> (n_accepted int32 [B], out_tokens int32 [B,G], margin_accept f64 [B], margin_sample f64 [B])."""
+    tl = np.ascontiguousarray(target_logits, dtype=np.float32)
+    B, G, V = tl.shape
+    gamma = G - 1
+    dl = np.ascontiguousarray(draft_logits, dtype=np.float32).reshape(B, gamma, V)
+    dt = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, gamma)
+    ua = np.ascontiguousarray(u_accept, dtype=np.float32).reshape(B, gamma)
+    us = np.ascontiguousarray(u_sample, dtype=np.float32).reshape(B)
+    n_acc = np.empty(B, dtype=np.int32)
+    out = np.empty((B, G), dtype=np.int32)
+    ma = np.empty(B, dtype=np.float64)
+    ms = np.empty(B, dtype=np.float64)
+    rc = _load().orc_accept(_p(tl, _f32p), _p(dl, _f32p), _p(dt, _i32p), B, G, V,
+                            ctypes.c_double(temperature), _p(ua, _f32p), _p(us, _f32p),
+                            _p(n_acc, _i32p), _p(out, _i32p), _p(ma, _f64p), _p(ms, _f64p))
+    if rc != 0:
+        raise ValueError("orc_accept: bad argument")
+    return n_acc, out, ma, ms
