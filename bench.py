@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-step attention path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload step128k]
+
+One "step" is one pass of the whole hot path over one batch of synthetic input, for all L
+layers: chunk summaries, retrieval-cache construction (score / top-k / gather), draft
+attention over the retrieval cache, verification attention over the full cache, then the two
+accept/resample calls (draft level and verification level). All inputs are resident in HBM
+before the timed region. Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="step128k")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=4, help="layers in the oracle's timed sample")
+    return ap.parse_args()
+
+
+class Step:
+    """Device buffers of one workload and the call sequence of one decode step."""
+
+    def __init__(self, w, L, device):
+        import paper_2404_11912_amd as tf
+        from paper_2404_11912_amd import synth
+        self.tf, self.w, self.L, self.dev = tf, w, L, device
+        B, H, N, d = w.B, w.H, w.N, w.d
+        self.layers = []
+        for l in range(L):
+            x = synth.make_workload_layer(w, l, device)
+            x["Q_d"] = x["Q"][:, :, -w.G_d:, :].contiguous()
+            x["Kmean"] = torch.empty((B, H, w.M, d), dtype=torch.float32, device=device)
+            x["Kr"] = torch.zeros((B, H, w.R, d), dtype=torch.bfloat16, device=device)
+            x["Vr"] = torch.zeros((B, H, w.R, d), dtype=torch.bfloat16, device=device)
+            x["idx"] = torch.empty((B, H, w.k), dtype=torch.int32, device=device)
+            x["O"] = torch.empty((B, H, w.G, d), dtype=torch.float32, device=device)
+            x["LSE"] = torch.empty((B, H, w.G), dtype=torch.float32, device=device)
+            x["O_d"] = torch.empty((B, H, w.G_d, d), dtype=torch.float32, device=device)
+            x["LSE_d"] = torch.empty((B, H, w.G_d), dtype=torch.float32, device=device)
+            self.layers.append(x)
+        T = w.temps[len(w.temps) // 2] if len(w.temps) > 1 else w.temps[0]
+        self.T = T
+        seed = synth.seed_for(w, 0) + 7
+        self.acc_verify = synth.make_accept_inputs(B, w.gamma, w.V, T, seed, correlated=True, device=device)
+        self.acc_draft = synth.make_accept_inputs(B, w.G_d - 1, w.V, T, seed + 1, correlated=False, device=device)
+        for a, G in ((self.acc_verify, w.G), (self.acc_draft, w.G_d)):
+            a["n"] = torch.empty((B,), dtype=torch.int32, device=device)
+            a["out"] = torch.empty((B, G), dtype=torch.int32, device=device)
+        nbytes = max(tf.tf_decode_attn_full_workspace_bytes(B, H, N, w.G),
+                     tf.tf_decode_attn_retrieval_workspace_bytes(B, H, w.R, w.G_d),
+                     tf.tf_chunk_topk_gather_workspace_bytes(B, H, w.M, w.k),
+                     tf.tf_spec_accept_workspace_bytes(B, w.G, w.V))
+        self.ws = tf.workspace(nbytes, device)
+
+    # the five calls, one layer each
+    def summarize(self, x):
+        self.tf.tf_chunk_summarize(x["K"], self.w.c, x["Kmean"], 0, self.w.M)
+
+    def topk_gather(self, x):
+        self.tf.tf_chunk_topk_gather(x["q_r"], x["Kmean"], x["K"], x["V"], self.w.c, self.w.k, x["idx"],
+                                     x["Kr"], x["Vr"], ws=self.ws)
+
+    def draft_attn(self, x):
+        self.tf.tf_decode_attn_retrieval(x["Q_d"], x["Kr"], x["Vr"], x["O_d"], x["LSE_d"], scale=1.0,
+                                         causal=True, ws=self.ws)
+
+    def verify_attn(self, x):
+        self.tf.tf_decode_attn_full(x["Q"], x["K"], x["V"], x["O"], x["LSE"], scale=1.0, causal=True,
+                                    ws=self.ws)
+
+    def accept(self, a):
+        self.tf.tf_spec_accept(a["target_logits"], a["draft_logits"], a["draft_tokens"], self.T,
+                               a["u_accept"], a["u_sample"], a["n"], a["out"], ws=self.ws)
+
+    def run(self, verify_events=None):
+        for x in self.layers:
+            self.summarize(x)
+            self.topk_gather(x)
+            self.draft_attn(x)
+            if verify_events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                self.verify_attn(x)
+                e1.record()
+                verify_events.append((e0, e1))
+            else:
+                self.verify_attn(x)
+        self.accept(self.acc_draft)
+        self.accept(self.acc_verify)
+
+    def breakdown(self, reps=3):
+        """Per-call device time (us per step, summed over layers), measured outside the timed region."""
+        names = ["chunk_summarize", "chunk_topk_gather", "decode_attn_retrieval", "decode_attn_full", "spec_accept"]
+        tot = dict.fromkeys(names, 0.0)
+        for _ in range(reps):
+            evs = []
+
+            def timed(name, fn, arg):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn(arg)
+                e1.record()
+                evs.append((name, e0, e1))
+            for x in self.layers:
+                timed("chunk_summarize", self.summarize, x)
+                timed("chunk_topk_gather", self.topk_gather, x)
+                timed("decode_attn_retrieval", self.draft_attn, x)
+                timed("decode_attn_full", self.verify_attn, x)
+            timed("spec_accept", self.accept, self.acc_draft)
+            timed("spec_accept", self.accept, self.acc_verify)
+            torch.cuda.synchronize()
+            for name, e0, e1 in evs:
+                tot[name] += e0.elapsed_time(e1) * 1e3
+        return {k: round(v / reps, 2) for k, v in tot.items()}
+
+
+def cpu_baseline(step, sample_layers):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: every call of the
+    path for all heads of the first `sample_layers` layers (copied to the host one layer at a
+    time, copies not timed), extrapolated to L layers; both accept calls are run whole."""
+    import oracle
+    from paper_2404_11912_amd import synth
+    w = step.w
+    cores = oracle.num_threads()
+    n_l = max(1, min(step.L, sample_layers))
+    t_layers = 0.0
+    for x in step.layers[:n_l]:
+        Ku, Vu, Qu = synth.as_u16(x["K"]), synth.as_u16(x["V"]), synth.as_u16(x["Q"])
+        t0 = time.perf_counter()
+        km = oracle.chunk_mean(Ku, w.c)
+        _, idx = oracle.retrieve(np.ascontiguousarray(Qu[:, :, -1, :]), km, w.k)
+        Kr, Vr = oracle.gather(Ku, Vu, idx, w.c)
+        oracle.attention(np.ascontiguousarray(Qu[:, :, -w.G_d:, :]), Kr, Vr, scale=1.0, causal=True)
+        oracle.attention(Qu, Ku, Vu, scale=1.0, causal=True)
+        t_layers += time.perf_counter() - t0
+        del Ku, Vu, km, Kr, Vr
+    t0 = time.perf_counter()
+    for a in (step.acc_draft, step.acc_verify):
+        oracle.accept(a["target_logits"].cpu().numpy(), a["draft_logits"].cpu().numpy(),
+                      a["draft_tokens"].cpu().numpy(), float(np.float32(step.T)),
+                      a["u_accept"].cpu().numpy(), a["u_sample"].cpu().numpy())
+    t_acc = time.perf_counter() - t0
+    us_step = (t_layers * (step.L / n_l) + t_acc) * 1e6
+    return {"value": round(us_step, 1), "unit": "us/step", "cores": cores, "kind": "oracle",
+            "sample": f"all path calls on all {w.H} heads of the first {n_l} of {step.L} layers "
+                      f"({t_layers:.2f} s, scaled x{step.L / n_l:g}) plus both accept calls "
+                      f"({t_acc * 1e3:.1f} ms)"}
+
+
+def read_traffic_note():
+    """HBM bytes per verification launch from the committed rocprofv3 counter summary, if any
+    (a line `traffic_bytes_per_launch: <number>` in profiles/attn_full_step128k_pmc.md)."""
+    path = os.path.join(ROOT, "profiles", "attn_full_step128k_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    from paper_2404_11912_amd import synth
+    w = synth.WORKLOADS[args.workload]
+    L = args.layers or w.L
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t_setup = time.perf_counter()
+    step = Step(w, L, dev)
+    torch.cuda.synchronize()
+    print(f"# inputs resident: {L} layers x {w.kv_bytes_per_layer() / 2**30:.2f} GiB KV "
+          f"in {time.perf_counter() - t_setup:.1f} s", file=sys.stderr, flush=True)
+
+    for _ in range(args.warmup):
+        step.run()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step.run(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kv_bytes_step = w.kv_bytes_per_layer() * L
+    verify_ms = [e0.elapsed_time(e1) for e0, e1 in events]
+    verify_avg_s = float(np.mean(verify_ms)) * 1e-3
+    achieved = w.kv_bytes_per_layer() / verify_avg_s / 1e9
+    breakdown = step.breakdown()
+    out = {
+        "metric": "decode-step attention latency (summaries + retrieval build + draft + verify + accept), 128K ctx",
+        "value": round(ms_per_step * 1e3, 1),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} L={L} H={w.H} N={w.N} d={w.d} chunk={w.c} budget={w.R} "
+                               f"G={w.G} G_draft={w.G_d} V={w.V} T={step.T}"},
+        "kv_gbps_whole_step": round(kv_bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
+        "breakdown_us_per_step": breakdown,
+        "roofline": {"bound": "hbm", "kernel": "attn_split_kernel (tf_decode_attn_full)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
+                     "algorithmic_bytes_per_launch": w.kv_bytes_per_layer(),
+                     "avg_launch_us": round(verify_avg_s * 1e6, 2), "launches_timed": len(verify_ms)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(step, args.cpu_sample_layers)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,180 @@
+/*
+ * triforce.h -- C ABI of the MI355X (gfx950) decode-step attention library for
+ * hierarchical speculative decoding with a retrieval cache (TriForce, arxiv 2404.11912).
+ *
+ * One call handles ONE transformer layer for all batch x head units; a decode step is L
+ * such calls. The five operations are the data-parallel hot path of Algorithm 1:
+ *
+ *   tf_chunk_summarize        average key of every KV chunk            (Sec. 4.1)
+ *   tf_chunk_topk_gather      score chunks by query . average key, keep the best k under a
+ *                             fixed budget, gather their K/V           (Sec. 4.1, Sec. 4.3)
+ *   tf_decode_attn_full       target model attention over the full cache C_p: verification of
+ *                             the speculated tokens                    (Algorithm 1, M_p(C_p,..))
+ *   tf_decode_attn_retrieval  the same attention over the retrieval cache C_r: self-drafting
+ *                                                                      (Algorithm 1, M_p(C_r,..))
+ *   tf_spec_accept            Verify / Correct / bonus token: lossless speculative sampling
+ *                                                                      (Algorithm 1, Sec. 4.2)
+ *
+ * Conventions (all calls)
+ *   - Every data pointer is a DEVICE pointer owned by the caller (the only host pointers are
+ *     the tf_kv_desc structs and strings). The library keeps no reference after return.
+ *   - Nothing is allocated, freed or synchronised: work is enqueued on the caller's HIP
+ *     stream, passed as `void* stream` (a hipStream_t; NULL = the default stream). Scratch
+ *     memory comes from a caller-provided workspace `ws` of at least the size the matching
+ *     *_workspace_bytes() query returns (256-byte aligned); calls sharing one workspace must
+ *     be ordered on one stream.
+ *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE fp32), fp32 is IEEE float.
+ *   - Strides are in ELEMENTS. head_dim must be 128 and contiguous (stride 1).
+ *   - Every call returns a status: TF_OK, or a negative TF_ERR_* after which nothing was
+ *     enqueued. Errors are detected on the host before launch; the library never aborts.
+ *   - Shapes are fixed per call and no call reads device memory on the host, so a sequence
+ *     of calls can be captured into a HIP graph.
+ */
+#ifndef TRIFORCE_H
+#define TRIFORCE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TF_OK 0
+#define TF_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, inconsistent shapes      */
+#define TF_ERR_UNSUPPORTED (-2) /* head_dim != 128, G > 8, k_chunks > 2048, ...              */
+#define TF_ERR_WORKSPACE (-3)   /* workspace missing, misaligned or too small                */
+#define TF_ERR_HIP (-4)         /* a HIP runtime call (kernel launch) reported an error      */
+
+#define TF_HEAD_DIM 128
+#define TF_MAX_QUERIES 8     /* G = gamma + 1 queries per attention call                     */
+#define TF_MAX_K_CHUNKS 2048 /* chunks kept by one tf_chunk_topk_gather call                 */
+#define TF_MAX_SPEC 16       /* G of tf_spec_accept                                          */
+
+/* A K or V cache tensor of one layer, bf16, indexed [b][h][t][0..head_dim).
+ * Element (b,h,t,j) lives at base + b*stride_b + h*stride_h + t*stride_t + j.
+ * The native layout [B,H,capacity,128] has stride_t = 128, stride_h = capacity*128,
+ * stride_b = heads*capacity*128. Base pointer and all strides must keep rows 16-byte
+ * aligned (strides multiples of 8 elements). K and V of one call share one descriptor. */
+typedef struct tf_kv_desc {
+    int32_t batch;
+    int32_t heads;    /* MHA: query heads = KV heads */
+    int32_t head_dim; /* must be TF_HEAD_DIM */
+    int32_t reserved; /* set to 0 */
+    int64_t capacity; /* allocated tokens per (b,h) */
+    int64_t stride_b, stride_h, stride_t;
+} tf_kv_desc;
+
+int tf_version(void);                   /* major*10000 + minor*100 + patch */
+const char *tf_status_string(int code); /* static string, never NULL */
+
+/* Tuning knobs (host state, not thread-safe against concurrent calls). Known names:
+ *   "attn_full_tokens_per_split", "attn_retr_tokens_per_split"  (multiples of 64; 0 = auto).
+ * Returns TF_ERR_INVALID_ARG for an unknown name or bad value. Workspace queries reflect the
+ * knobs in force when they are called. */
+int tf_set_option(const char *name, int64_t value);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_chunk_summarize -- Sec. 4.1: "the average key cache within each chunk".
+ *   Kmean[b,h,m,:] = (1/chunk) * sum_{i<chunk} K[b,h,m*chunk+i,:]   for
+ *   m in [first_chunk, first_chunk+n_chunks), every (b,h). fp32 sums of bf16 keys.
+ *   K      in   bf16, described by kd; (first_chunk+n_chunks)*chunk <= kd->capacity
+ *   Kmean  out  fp32 [batch, heads, M_cap, 128] contiguous; other rows untouched
+ *   The range arguments allow summarising only newly completed chunks. n_chunks == 0 is a
+ *   no-op. chunk in [1, 64].
+ * ------------------------------------------------------------------------------------- */
+int tf_chunk_summarize(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t first_chunk,
+                       int64_t n_chunks, float *Kmean, int64_t M_cap, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_chunk_topk_gather -- Sec. 4.1 / Sec. 4.3: retrieval-cache construction.
+ *   score[b,h,m] = sum_j q_r[b,h,j] * Kmean[b,h,m,j] (raw dot product, fp32), for
+ *   m < n[b], n[b] = n_chunks ? n_chunks[b] : n_chunks_all (n_chunks_all is always an upper
+ *   bound of n[b] and <= M_cap). The k_chunks highest-scoring chunks are kept in descending
+ *   score order, equal scores toward the lower chunk index. Then, for j < k_chunks, i < chunk:
+ *     Kr[b,h,j*chunk+i,:] = K[b,h,out_idx[b,h,j]*chunk+i,:]   (same for V), bit-exact copies.
+ *   q_r       in   bf16 [batch, heads, 128]
+ *   Kmean     in   fp32 [batch, heads, M_cap, 128] (from tf_chunk_summarize)
+ *   K, V      in   bf16, described by kd
+ *   n_chunks  in   int32 [batch] device array, or NULL
+ *   out_idx   out  int32 [batch, heads, k_chunks]
+ *   out_score out  fp32  [batch, heads, k_chunks] or NULL
+ *   Kr, Vr    out  bf16, described by rd (same batch/heads as kd, capacity >= k_chunks*chunk);
+ *                  rows >= k_chunks*chunk untouched. Kr == NULL && Vr == NULL skips the gather.
+ *   If n[b] < k_chunks on the device, only n[b] chunks are kept: the remaining out_idx slots
+ *   are -1 (scores -inf) and the corresponding cache rows are left untouched.
+ *   1 <= k_chunks <= min(n_chunks_all, TF_MAX_K_CHUNKS); chunk in [1, 64].
+ * ------------------------------------------------------------------------------------- */
+size_t tf_chunk_topk_gather_workspace_bytes(int32_t batch, int32_t heads, int64_t n_chunks_all,
+                                            int32_t k_chunks);
+int tf_chunk_topk_gather(const void *q_r, const float *Kmean, int64_t M_cap, const void *K,
+                         const void *V, const tf_kv_desc *kd, int32_t chunk,
+                         const int32_t *n_chunks, int64_t n_chunks_all, int32_t k_chunks,
+                         int32_t *out_idx, float *out_score, void *Kr, void *Vr,
+                         const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_decode_attn_full -- Algorithm 1, "Run M_p with full cache C_p": attention of the
+ * G = gamma+1 speculated query tokens of one layer over the whole KV cache.
+ *   len[b] = kv_len ? kv_len[b] : kv_len_all (kv_len_all is always an upper bound of len[b]
+ *   and <= kd->capacity). For every (b,h,g), with n_g = causal ? len[b]-G+1+g : len[b]
+ *   (the G queries are the last G tokens already appended to the cache):
+ *     z_t = scale * <Q[b,h,g,:], K[b,h,t,:]>, t < n_g ;  O[b,h,g,:] = softmax_t(z) . V ;
+ *     LSE[b,h,g] = log sum_t exp(z_t)   (natural log).
+ *   Q       in   bf16 [batch, heads, G, 128] contiguous
+ *   K, V    in   bf16, described by kd
+ *   kv_len  in   int32 [batch] device array, or NULL
+ *   O       out  fp32 [batch, heads, G, 128];  LSE out fp32 [batch, heads, G] or NULL
+ *   bf16 inputs, fp32 accumulation. A query with no visible key (n_g <= 0) gets O = 0,
+ *   LSE = -inf. 1 <= G <= TF_MAX_QUERIES; causal requires kv_len_all >= G.
+ * ------------------------------------------------------------------------------------- */
+size_t tf_decode_attn_full_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all,
+                                           int32_t G);
+int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                        const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
+                        int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes,
+                        void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_decode_attn_retrieval -- Algorithm 1, "Run M_p with retrieval cache C_r": the same
+ * attention over the gathered retrieval cache (K, V are Kr, Vr; kv_len is the number of valid
+ * cache rows, budget plus any tokens the caller appended). Same arguments and semantics as
+ * tf_decode_attn_full; tuned for short caches (launch-latency regime).
+ * ------------------------------------------------------------------------------------- */
+size_t tf_decode_attn_retrieval_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all,
+                                                int32_t G);
+int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                             const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
+                             int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes,
+                             void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_spec_accept -- Algorithm 1, Verify / Correct / "sample next token" lines, i.e. the
+ * standard lossless speculative-sampling rule (Sec. 4.2 "Correctness"). One sequence per b,
+ * gamma = G-1 drafted tokens. With p_i = softmax(target_logits[b,i]/T),
+ * q_i = softmax(draft_logits[b,i]/T) (computed in fp64):
+ *   walk i = 0..gamma-1, x = draft_tokens[b,i]: accept iff u_accept[b,i]*q_i[x] < p_i[x];
+ *   at the first reject draw from norm(max(p_i-q_i,0)) (from p_i if that is all zero);
+ *   if none is rejected draw from p_gamma. Draws are inverse-CDF in index order at
+ *   u_sample[b]: the smallest v whose cumulative mass exceeds u_sample*total.
+ *   T == 0: p, q are one-hot at the first arg-max: accept iff x == argmax target row;
+ *   correction / bonus = that arg-max.
+ *   target_logits in fp32 [B, G, V];  draft_logits in fp32 [B, G-1, V]
+ *   draft_tokens  in int32 [B, G-1] in [0,V) (out-of-range tokens are rejected)
+ *   u_accept      in fp32 [B, G-1] in [0,1);  u_sample in fp32 [B] in [0,1)
+ *   n_accepted    out int32 [B];  out_tokens out int32 [B, G]: the accepted tokens, then the
+ *                 drawn token, then -1.
+ *   1 <= G <= TF_MAX_SPEC (G == 1: no drafted token, pointers to empty arrays may be NULL),
+ *   V >= 1, temperature >= 0.
+ * ------------------------------------------------------------------------------------- */
+size_t tf_spec_accept_workspace_bytes(int32_t B, int32_t G, int32_t V);
+int tf_spec_accept(const float *target_logits, const float *draft_logits,
+                   const int32_t *draft_tokens, int32_t B, int32_t G, int32_t V,
+                   float temperature, const float *u_accept, const float *u_sample,
+                   int32_t *n_accepted, int32_t *out_tokens, void *ws, size_t ws_bytes,
+                   void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRIFORCE_H */

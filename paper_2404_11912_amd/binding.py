@@ -1,0 +1,263 @@
+"""ctypes binding of libtriforce_hip.so: same names as the C ABI, argument marshalling only.
+
+Every step runs in the HIP kernels; PyTorch is used for device memory and the current
+stream. There is no CPU fallback: if the library is missing or a call fails, an exception
+is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtriforce_hip.so")
+
+TF_OK = 0
+TF_MAX_QUERIES = 8
+TF_MAX_K_CHUNKS = 2048
+TF_MAX_SPEC = 16
+
+EXPORTS = (
+    "tf_version", "tf_status_string", "tf_set_option",
+    "tf_chunk_summarize",
+    "tf_chunk_topk_gather_workspace_bytes", "tf_chunk_topk_gather",
+    "tf_decode_attn_full_workspace_bytes", "tf_decode_attn_full",
+    "tf_decode_attn_retrieval_workspace_bytes", "tf_decode_attn_retrieval",
+    "tf_spec_accept_workspace_bytes", "tf_spec_accept",
+)
+
+
+class TfError(RuntimeError):
+    def __init__(self, call: str, code: int, text: str):
+        super().__init__(f"{call} failed: {text} ({code})")
+        self.code = code
+
+
+class tf_kv_desc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("capacity", ctypes.c_int64),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_t", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built shared library (fails loudly when it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           "`python -m paper_2404_11912_amd.build` (there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    dp = ctypes.POINTER(tf_kv_desc)
+    lib.tf_version.restype = ctypes.c_int
+    lib.tf_version.argtypes = []
+    lib.tf_status_string.restype = ctypes.c_char_p
+    lib.tf_status_string.argtypes = [ctypes.c_int]
+    lib.tf_set_option.restype = ctypes.c_int
+    lib.tf_set_option.argtypes = [ctypes.c_char_p, i64]
+    lib.tf_chunk_summarize.restype = ctypes.c_int
+    lib.tf_chunk_summarize.argtypes = [vp, dp, i32, i64, i64, vp, i64, vp]
+    lib.tf_chunk_topk_gather_workspace_bytes.restype = sz
+    lib.tf_chunk_topk_gather_workspace_bytes.argtypes = [i32, i32, i64, i32]
+    lib.tf_chunk_topk_gather.restype = ctypes.c_int
+    lib.tf_chunk_topk_gather.argtypes = [vp, vp, i64, vp, vp, dp, i32, vp, i64, i32, vp, vp, vp, vp, dp,
+                                         vp, sz, vp]
+    for name in ("tf_decode_attn_full", "tf_decode_attn_retrieval"):
+        getattr(lib, name + "_workspace_bytes").restype = sz
+        getattr(lib, name + "_workspace_bytes").argtypes = [i32, i32, i64, i32]
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, i32, vp, vp, vp, sz, vp]
+    lib.tf_spec_accept_workspace_bytes.restype = sz
+    lib.tf_spec_accept_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.tf_spec_accept.restype = ctypes.c_int
+    lib.tf_spec_accept.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(call: str, code: int):
+    if code != TF_OK:
+        raise TfError(call, code, load_library().tf_status_string(code).decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _need(t: torch.Tensor, dtype, name: str, contiguous=True):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if contiguous and not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def kv_desc(t: torch.Tensor) -> tf_kv_desc:
+    """Descriptor of a bf16 cache tensor indexed [b][h][t][d] (any strides with d contiguous)."""
+    _need(t, torch.bfloat16, "cache", contiguous=False)
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("cache must be 4-D [B,H,N,d] with a contiguous last dim")
+    B, H, N, d = t.shape
+    return tf_kv_desc(B, H, d, 0, N, t.stride(0), t.stride(1), t.stride(2))
+
+
+def workspace(nbytes: int, device) -> torch.Tensor:
+    """A 256-byte aligned scratch buffer (torch's caching allocator aligns to >= 512 B)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def tf_version() -> int:
+    return int(load_library().tf_version())
+
+
+def tf_set_option(name: str, value: int) -> None:
+    _check("tf_set_option", load_library().tf_set_option(name.encode(), int(value)))
+
+
+def tf_chunk_summarize(K, chunk: int, Kmean, first_chunk: int = 0, n_chunks: int | None = None, stream=None):
+    """Kmean[b,h,m,:] = mean of K[b,h,m*chunk:(m+1)*chunk,:] for m in [first_chunk, first_chunk+n_chunks)."""
+    lib = load_library()
+    _need(Kmean, torch.float32, "Kmean")
+    d = kv_desc(K)
+    if Kmean.dim() != 4 or Kmean.shape[0] != d.batch or Kmean.shape[1] != d.heads or Kmean.shape[3] != d.head_dim:
+        raise ValueError("Kmean must be [B,H,M_cap,d]")
+    M_cap = Kmean.shape[2]
+    if n_chunks is None:
+        n_chunks = min(M_cap, K.shape[2] // chunk) - first_chunk
+    _check("tf_chunk_summarize",
+           lib.tf_chunk_summarize(_ptr(K), ctypes.byref(d), int(chunk), int(first_chunk), int(n_chunks),
+                                  _ptr(Kmean), int(M_cap), _stream(stream)))
+    return Kmean
+
+
+def tf_chunk_topk_gather_workspace_bytes(batch: int, heads: int, n_chunks_all: int, k_chunks: int) -> int:
+    return int(load_library().tf_chunk_topk_gather_workspace_bytes(batch, heads, n_chunks_all, k_chunks))
+
+
+def tf_chunk_topk_gather(q_r, Kmean, K, V, chunk: int, k_chunks: int, out_idx, Kr=None, Vr=None,
+                         out_score=None, n_chunks=None, n_chunks_all: int | None = None, ws=None, stream=None):
+    """Score chunks by q_r . Kmean, keep the k_chunks best (descending), gather their K/V into Kr/Vr."""
+    lib = load_library()
+    _need(q_r, torch.bfloat16, "q_r")
+    _need(Kmean, torch.float32, "Kmean")
+    _need(out_idx, torch.int32, "out_idx")
+    d = kv_desc(K)
+    kv_desc(V)
+    if V.stride() != K.stride() or V.shape != K.shape:
+        raise ValueError("K and V must share shape and strides")
+    M_cap = Kmean.shape[2]
+    if n_chunks_all is None:
+        n_chunks_all = min(M_cap, K.shape[2] // chunk)
+    if n_chunks is not None:
+        _need(n_chunks, torch.int32, "n_chunks")
+    if out_score is not None:
+        _need(out_score, torch.float32, "out_score")
+    rd = None
+    if Kr is not None or Vr is not None:
+        rd = kv_desc(Kr)
+        kv_desc(Vr)
+        if Vr.stride() != Kr.stride() or Vr.shape != Kr.shape:
+            raise ValueError("Kr and Vr must share shape and strides")
+    if ws is None:
+        ws = workspace(tf_chunk_topk_gather_workspace_bytes(d.batch, d.heads, n_chunks_all, k_chunks), K.device)
+    _check("tf_chunk_topk_gather",
+           lib.tf_chunk_topk_gather(_ptr(q_r), _ptr(Kmean), int(M_cap), _ptr(K), _ptr(V), ctypes.byref(d),
+                                    int(chunk), _ptr(n_chunks), int(n_chunks_all), int(k_chunks),
+                                    _ptr(out_idx), _ptr(out_score), _ptr(Kr), _ptr(Vr),
+                                    ctypes.byref(rd) if rd is not None else None,
+                                    _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+    return out_idx
+
+
+def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream):
+    lib = load_library()
+    _need(Q, torch.bfloat16, "Q")
+    _need(O, torch.float32, "O")
+    d = kv_desc(K)
+    kv_desc(V)
+    if V.stride() != K.stride() or V.shape != K.shape:
+        raise ValueError("K and V must share shape and strides")
+    if Q.dim() != 4 or Q.shape[0] != d.batch or Q.shape[1] != d.heads or Q.shape[3] != d.head_dim:
+        raise ValueError("Q must be [B,H,G,d]")
+    G = Q.shape[2]
+    if tuple(O.shape) != tuple(Q.shape):
+        raise ValueError("O must be [B,H,G,d]")
+    if LSE is not None:
+        _need(LSE, torch.float32, "LSE")
+        if tuple(LSE.shape) != tuple(Q.shape[:3]):
+            raise ValueError("LSE must be [B,H,G]")
+    if kv_len is not None:
+        _need(kv_len, torch.int32, "kv_len")
+    if kv_len_all is None:
+        kv_len_all = K.shape[2]
+    if ws is None:
+        nbytes = getattr(lib, name + "_workspace_bytes")(d.batch, d.heads, int(kv_len_all), int(G))
+        ws = workspace(nbytes, K.device)
+    _check(name, getattr(lib, name)(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(kv_len), int(kv_len_all),
+                                    int(G), float(scale), int(bool(causal)), _ptr(O), _ptr(LSE), _ptr(ws),
+                                    ws.numel() * ws.element_size(), _stream(stream)))
+    return O
+
+
+def tf_decode_attn_full_workspace_bytes(batch: int, heads: int, kv_len_all: int, G: int) -> int:
+    return int(load_library().tf_decode_attn_full_workspace_bytes(batch, heads, kv_len_all, G))
+
+
+def tf_decode_attn_retrieval_workspace_bytes(batch: int, heads: int, kv_len_all: int, G: int) -> int:
+    return int(load_library().tf_decode_attn_retrieval_workspace_bytes(batch, heads, kv_len_all, G))
+
+
+def tf_decode_attn_full(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None, scale: float = 1.0,
+                        causal: bool = True, ws=None, stream=None):
+    """Verification attention: G queries [B,H,G,d] over the full cache K,V [B,H,N,d] -> O fp32, LSE fp32."""
+    return _attn("tf_decode_attn_full", Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream)
+
+
+def tf_decode_attn_retrieval(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None, scale: float = 1.0,
+                             causal: bool = True, ws=None, stream=None):
+    """Draft attention: the same operation over the retrieval cache (K, V = Kr, Vr)."""
+    return _attn("tf_decode_attn_retrieval", Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream)
+
+
+def tf_spec_accept_workspace_bytes(B: int, G: int, V: int) -> int:
+    return int(load_library().tf_spec_accept_workspace_bytes(B, G, V))
+
+
+def tf_spec_accept(target_logits, draft_logits, draft_tokens, temperature: float, u_accept, u_sample,
+                   n_accepted, out_tokens, ws=None, stream=None):
+    """Verify / Correct / bonus token for B sequences: fills n_accepted [B] and out_tokens [B,G]."""
+    lib = load_library()
+    _need(target_logits, torch.float32, "target_logits")
+    B, G, V = target_logits.shape
+    if G > 1:
+        _need(draft_logits, torch.float32, "draft_logits")
+        _need(draft_tokens, torch.int32, "draft_tokens")
+        _need(u_accept, torch.float32, "u_accept")
+        if tuple(draft_logits.shape) != (B, G - 1, V) or tuple(draft_tokens.shape) != (B, G - 1) \
+                or tuple(u_accept.shape) != (B, G - 1):
+            raise ValueError("draft tensors must be [B,G-1,V] / [B,G-1]")
+    _need(u_sample, torch.float32, "u_sample")
+    _need(n_accepted, torch.int32, "n_accepted")
+    _need(out_tokens, torch.int32, "out_tokens")
+    if tuple(u_sample.shape) != (B,) or tuple(n_accepted.shape) != (B,) or tuple(out_tokens.shape) != (B, G):
+        raise ValueError("u_sample / n_accepted must be [B], out_tokens [B,G]")
+    if ws is None:
+        ws = workspace(tf_spec_accept_workspace_bytes(B, G, V), target_logits.device)
+    _check("tf_spec_accept",
+           lib.tf_spec_accept(_ptr(target_logits), _ptr(draft_logits) if G > 1 else None,
+                              _ptr(draft_tokens) if G > 1 else None, B, G, V, float(temperature),
+                              _ptr(u_accept) if G > 1 else None, _ptr(u_sample), _ptr(n_accepted),
+                              _ptr(out_tokens), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+    return n_accepted, out_tokens

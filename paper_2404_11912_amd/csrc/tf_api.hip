@@ -1,0 +1,92 @@
+// extern "C" entry points declared in include/triforce.h. Argument checks and kernel launches
+// live next to each kernel; this file only forwards.
+#include <string.h>
+
+#include "tf_common.hpp"
+
+namespace tf {
+int summarize_launch(const void *, const tf_kv_desc *, int32_t, int64_t, int64_t, float *, int64_t, void *);
+size_t topk_workspace_bytes(int32_t, int32_t, int64_t, int32_t);
+int topk_gather_launch(const void *, const float *, int64_t, const void *, const void *, const tf_kv_desc *, int32_t,
+                       const int32_t *, int64_t, int32_t, int32_t *, float *, void *, void *, const tf_kv_desc *,
+                       void *, size_t, void *);
+size_t attn_workspace_bytes(int32_t, int32_t, int64_t, int32_t, bool);
+int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, const int32_t *, int64_t, int32_t,
+                float, int32_t, float *, float *, void *, size_t, void *, bool);
+int set_attn_option(bool retrieval, int64_t v);
+size_t accept_workspace_bytes(int32_t, int32_t, int32_t);
+int accept_launch(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, float, const float *,
+                  const float *, int32_t *, int32_t *, void *, size_t, void *);
+}  // namespace tf
+
+extern "C" {
+
+int tf_version(void) { return 100; /* 0.1.0 */ }
+
+const char *tf_status_string(int code) {
+    switch (code) {
+        case TF_OK: return "ok";
+        case TF_ERR_INVALID_ARG: return "invalid argument";
+        case TF_ERR_UNSUPPORTED: return "unsupported shape or size";
+        case TF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TF_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int tf_set_option(const char *name, int64_t value) {
+    if (!name) return TF_ERR_INVALID_ARG;
+    if (!strcmp(name, "attn_full_tokens_per_split")) return tf::set_attn_option(false, value);
+    if (!strcmp(name, "attn_retr_tokens_per_split")) return tf::set_attn_option(true, value);
+    return TF_ERR_INVALID_ARG;
+}
+
+int tf_chunk_summarize(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t first_chunk, int64_t n_chunks,
+                       float *Kmean, int64_t M_cap, void *stream) {
+    return tf::summarize_launch(K, kd, chunk, first_chunk, n_chunks, Kmean, M_cap, stream);
+}
+
+size_t tf_chunk_topk_gather_workspace_bytes(int32_t batch, int32_t heads, int64_t n_chunks_all, int32_t k_chunks) {
+    return tf::topk_workspace_bytes(batch, heads, n_chunks_all, k_chunks);
+}
+
+int tf_chunk_topk_gather(const void *q_r, const float *Kmean, int64_t M_cap, const void *K, const void *V,
+                         const tf_kv_desc *kd, int32_t chunk, const int32_t *n_chunks, int64_t n_chunks_all,
+                         int32_t k_chunks, int32_t *out_idx, float *out_score, void *Kr, void *Vr,
+                         const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream) {
+    return tf::topk_gather_launch(q_r, Kmean, M_cap, K, V, kd, chunk, n_chunks, n_chunks_all, k_chunks, out_idx,
+                                  out_score, Kr, Vr, rd, ws, ws_bytes, stream);
+}
+
+size_t tf_decode_attn_full_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G) {
+    return tf::attn_workspace_bytes(batch, heads, kv_len_all, G, false);
+}
+
+int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
+                        int64_t kv_len_all, int32_t G, float scale, int32_t causal, float *O, float *LSE, void *ws,
+                        size_t ws_bytes, void *stream) {
+    return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, false);
+}
+
+size_t tf_decode_attn_retrieval_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G) {
+    return tf::attn_workspace_bytes(batch, heads, kv_len_all, G, true);
+}
+
+int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                             const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale, int32_t causal,
+                             float *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
+    return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, true);
+}
+
+size_t tf_spec_accept_workspace_bytes(int32_t B, int32_t G, int32_t V) {
+    return tf::accept_workspace_bytes(B, G, V);
+}
+
+int tf_spec_accept(const float *target_logits, const float *draft_logits, const int32_t *draft_tokens, int32_t B,
+                   int32_t G, int32_t V, float temperature, const float *u_accept, const float *u_sample,
+                   int32_t *n_accepted, int32_t *out_tokens, void *ws, size_t ws_bytes, void *stream) {
+    return tf::accept_launch(target_logits, draft_logits, draft_tokens, B, G, V, temperature, u_accept, u_sample,
+                             n_accepted, out_tokens, ws, ws_bytes, stream);
+}
+
+}  // extern "C"

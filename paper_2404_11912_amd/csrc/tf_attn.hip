@@ -1,0 +1,349 @@
+// tf_decode_attn_full / tf_decode_attn_retrieval: attention of G <= 8 speculated query tokens
+// over a long bf16 KV cache (Algorithm 1: the M_p(C_p, ...) verification pass and the
+// M_p(C_r, ...) drafting pass).
+//
+// Design (gfx950, wave64): flash-decoding. The KV sequence of every (b,h) is cut into
+// `nsplit` contiguous ranges, one 256-thread workgroup each; its 4 waves walk interleaved
+// 16-token tiles, so the workgroup streams K and V front to back. Per tile and wave:
+//   * K rows arrive as MFMA A-operands (lane (r,s): token r, dims 32kk+8s..+8) and four
+//     v_mfma_f32_16x16x32_bf16 give S^T[token, query] against the resident Q operand;
+//   * the accumulator layout (lane (r,s), reg i = token 4s+i, query r) is exactly the
+//     A-operand layout of v_mfma_f32_16x16x4_f32, so P = exp2(S - m) feeds the PV product
+//     with no data movement; V rows arrive fully coalesced (lane (r,s): token 4s+i, dims
+//     8r..8r+8), are widened bf16->fp32 in registers and serve as B-operands. P and V stay
+//     fp32, so the only rounding is fp32 accumulation.
+//   * online softmax: the per-query running maximum is reduced over the tile with two
+//     wave shuffles; accumulators are rescaled only when a maximum actually grows.
+// The 4 waves merge (m, l, O) through LDS and write one fp32 partial per split; a small
+// second kernel merges the splits by log-sum-exp and normalises.
+#include "tf_common.hpp"
+
+namespace tf {
+
+constexpr int kTile = 16;    // tokens per MFMA tile
+constexpr int kWaves = 4;    // waves per workgroup
+constexpr int kGPad = 8;     // query rows kept in the partials
+
+struct AttnParams {
+    const uint16_t *Q, *K, *V;
+    int64_t sb, sh, st;
+    const int32_t *kv_len;
+    int32_t kv_len_all;
+    int32_t H, G, causal;
+    int32_t nsplit, tokens_per_split;
+    float scale_log2;
+    float *part_o;   // [BH][nsplit][kGPad][128]
+    float *part_ml;  // [BH][nsplit][2][kGPad]   (running max in log2 units, then sum)
+};
+
+__device__ __forceinline__ float safe_max(float m) { return m == -INFINITY ? 0.0f : m; }
+
+__global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
+    const int r = lane & 15, s = lane >> 4;
+    const int split = blockIdx.x % p.nsplit;
+    const int bh = blockIdx.x / p.nsplit;
+    const int b = bh / p.H, h = bh - b * p.H;
+
+    int len = p.kv_len ? p.kv_len[b] : p.kv_len_all;
+    len = min(max(len, 0), p.kv_len_all);
+    const int64_t tb64 = (int64_t)split * p.tokens_per_split;
+    const int t_begin = (int)(tb64 < (int64_t)len ? tb64 : (int64_t)len);
+    const int t_end = (int)(tb64 + p.tokens_per_split < (int64_t)len ? tb64 + p.tokens_per_split : (int64_t)len);
+    const int last_row = max(len - 1, 0);
+
+    // uniform base pointers + 32-bit per-lane byte offsets (scalar-base addressing)
+    const char *Kb = reinterpret_cast<const char *>(p.K + (int64_t)b * p.sb + (int64_t)h * p.sh);
+    const char *Vb = reinterpret_cast<const char *>(p.V + (int64_t)b * p.sb + (int64_t)h * p.sh);
+    const int64_t row_bytes = p.st * 2;
+    const uint32_t k_off = (uint32_t)(r * row_bytes + s * 16);  // K: token r, dims 8s.. (+64 B per kk)
+    uint32_t v_off[4];                                          // V: token 4s+i, dims 8r..
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v_off[i] = (uint32_t)((4 * s + i) * row_bytes + r * 16);
+
+    // resident Q operand: lane (r,s) holds Q[query r][32kk + 8s .. +8], zero for r >= G
+    uint4 qb[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        qb[kk] = make_uint4(0, 0, 0, 0);
+        if (r < p.G) qb[kk] = ld16(p.Q + ((int64_t)bh * p.G + r) * kHeadDim + kk * 32 + s * 8);
+    }
+
+    // tokens < n_all are visible to every query; this lane's query sees tokens < n_mine
+    const int n_all = p.causal ? len - p.G + 1 : len;
+    const int n_mine = (p.causal && r < p.G) ? len - p.G + 1 + r : len;
+
+    f32x4_t o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    auto load_k = [&](int t0, uint4(&k)[4]) {
+        const char *base = Kb + (int64_t)t0 * row_bytes;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) k[kk] = ld16(base + k_off + kk * 64);
+    };
+    auto load_v = [&](int t0, uint4(&v)[4]) {
+        const char *base = Vb + (int64_t)t0 * row_bytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = ld16(base + v_off[i]);
+    };
+
+    // S^T tile: four bf16 MFMAs over the head dim, then the log2-domain scale
+    auto qk_tile = [&](const uint4(&k)[4], float(&z)[4]) {
+        f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k[kk]),
+                                                         __builtin_bit_cast(bf16x8_t, qb[kk]), sc, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) z[i] = sc[i] * p.scale_log2;
+    };
+
+    // online softmax of one tile and the P.V product
+    auto softmax_pv = [&](int t0, float(&z)[4], const uint4(&v)[4]) {
+        if (t0 + kTile > n_all) {  // wave-uniform: only tiles that touch the causal / ragged tail
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (t0 + 4 * s + i >= n_mine) z[i] = -INFINITY;
+        }
+        float mt = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+        mt = wave_max_xor(mt, 16);
+        mt = wave_max_xor(mt, 32);
+        const float m_new = fmaxf(m_run, mt);
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some query's maximum grew
+            const float alpha = __builtin_amdgcn_exp2f(m_run - safe_max(m_new));
+            l_run *= alpha;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float aj = __shfl(alpha, 4 * s + j, kWave);  // factor of query 4s+j
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e][j] *= aj;
+            }
+            m_run = m_new;
+        }
+        const float ms = safe_max(m_run);
+        float pr[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pr[i] = __builtin_amdgcn_exp2f(z[i] - ms);
+        l_run += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float vf = (e & 1) ? bf16hi(w[e >> 1]) : bf16lo(w[e >> 1]);
+                o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[i], vf, o[e], 0, 0, 0);
+            }
+        }
+    };
+
+    // Whole 16-token tiles of this split, interleaved over the 4 waves. K of the next tile is
+    // requested before the current QK^T, V of the next tile right after it (when the current
+    // K registers are dead), so one tile of loads is always in flight per wave.
+    const int n_full = (t_end - t_begin) / kTile;            // whole tiles in the split
+    const int n_mine_tiles = (n_full - wave + kWaves - 1) / kWaves;
+    if (n_mine_tiles > 0) {
+        constexpr int step = kWaves * kTile;
+        uint4 ka[4], va[4], kb2[4], vb2[4];
+        float z[4];
+        int t0 = t_begin + wave * kTile;
+        int left = n_mine_tiles;  // tiles not yet computed; buffer A always holds the next one
+        load_k(t0, ka);
+        load_v(t0, va);
+        // steady state: no conditional loads, so the wait counters stay exact
+        while (left > 2) {
+            load_k(t0 + step, kb2);
+            qk_tile(ka, z);
+            load_v(t0 + step, vb2);
+            softmax_pv(t0, z, va);
+            load_k(t0 + 2 * step, ka);
+            qk_tile(kb2, z);
+            load_v(t0 + 2 * step, va);
+            softmax_pv(t0 + step, z, vb2);
+            t0 += 2 * step;
+            left -= 2;
+        }
+        if (left == 2) {
+            load_k(t0 + step, kb2);
+            qk_tile(ka, z);
+            load_v(t0 + step, vb2);
+            softmax_pv(t0, z, va);
+            qk_tile(kb2, z);
+            softmax_pv(t0 + step, z, vb2);
+        } else {
+            qk_tile(ka, z);
+            softmax_pv(t0, z, va);
+        }
+    }
+    // ragged tail (len not a multiple of 16): one partial tile, rows clamped to the last valid
+    // token and masked; handled by the wave whose turn it would be
+    if (t_begin + n_full * kTile < t_end && (n_full % kWaves) == wave) {
+        const int t0 = t_begin + n_full * kTile;
+        uint4 kt[4], vt[4];
+        float z[4];
+        const char *kp = Kb + (int64_t)min(t0 + r, last_row) * row_bytes + s * 16;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kt[kk] = ld16(kp + kk * 64);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            vt[i] = ld16(Vb + (int64_t)min(t0 + 4 * s + i, last_row) * row_bytes + r * 16);
+        qk_tile(kt, z);
+        softmax_pv(t0, z, vt);
+    }
+
+    // total of the per-lane partial sums of each query (lanes (r, 0..3))
+    l_run += __shfl_xor(l_run, 16, kWave);
+    l_run += __shfl_xor(l_run, 32, kWave);
+
+    __shared__ float sm_o[kWaves][kGPad][kHeadDim];
+    __shared__ float sm_m[kWaves][16];
+    __shared__ float sm_l[kWaves][16];
+    if (s == 0) {
+        sm_m[wave][r] = m_run;
+        sm_l[wave][r] = l_run;
+    }
+    if (s < 2) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float4 lo = make_float4(o[0][j], o[1][j], o[2][j], o[3][j]);
+            float4 hi = make_float4(o[4][j], o[5][j], o[6][j], o[7][j]);
+            float *dst = &sm_o[wave][4 * s + j][8 * r];
+            *reinterpret_cast<float4 *>(dst) = lo;
+            *reinterpret_cast<float4 *>(dst + 4) = hi;
+        }
+    }
+    __syncthreads();
+
+    const int64_t pbase = (int64_t)bh * p.nsplit + split;
+    for (int idx = tid; idx < p.G * kHeadDim; idx += 256) {
+        const int g = idx >> 7, dim = idx & 127;
+        float mw[kWaves], M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            mw[w] = sm_m[w][g];
+            M = fmaxf(M, mw[w]);
+        }
+        const float Ms = safe_max(M);
+        float acc = 0.f, lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float a = __builtin_amdgcn_exp2f(mw[w] - Ms);
+            acc += a * sm_o[w][g][dim];
+            lsum += a * sm_l[w][g];
+        }
+        p.part_o[(pbase * kGPad + g) * kHeadDim + dim] = acc;
+        if (dim == 0) {
+            p.part_ml[(pbase * 2 + 0) * kGPad + g] = M;
+            p.part_ml[(pbase * 2 + 1) * kGPad + g] = lsum;
+        }
+    }
+}
+
+// merge the split partials of one (b,h,g): one 128-thread block, thread = output dim
+__global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restrict__ part_o,
+                                                           const float *__restrict__ part_ml,
+                                                           int nsplit, int G, float *__restrict__ O,
+                                                           float *__restrict__ LSE) {
+    const int bh = blockIdx.x / G, g = blockIdx.x - bh * G;
+    const int dim = threadIdx.x;
+    const int64_t base = (int64_t)bh * nsplit;
+    float M = -INFINITY;
+    for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, part_ml[((base + sp) * 2 + 0) * kGPad + g]);
+    const float Ms = safe_max(M);
+    float L = 0.f, acc = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const float a = __builtin_amdgcn_exp2f(part_ml[((base + sp) * 2 + 0) * kGPad + g] - Ms);
+        L += a * part_ml[((base + sp) * 2 + 1) * kGPad + g];
+        acc += a * part_o[((base + sp) * kGPad + g) * kHeadDim + dim];
+    }
+    const int64_t row = (int64_t)bh * G + g;
+    O[row * kHeadDim + dim] = L > 0.f ? acc / L : 0.f;
+    if (LSE && dim == 0) LSE[row] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+}
+
+struct SplitPlan {
+    int nsplit;
+    int tokens_per_split;
+};
+
+static int64_t g_tps_full = 0, g_tps_retr = 0;  // 0 = automatic
+
+int set_attn_option(bool retrieval, int64_t v) {
+    if (v < 0 || (v % 64) != 0 || v > (1 << 30)) return TF_ERR_INVALID_ARG;
+    (retrieval ? g_tps_retr : g_tps_full) = v;
+    return TF_OK;
+}
+
+static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, bool retrieval) {
+    int64_t tps = retrieval ? g_tps_retr : g_tps_full;
+    if (tps == 0) {
+        // enough workgroups to oversubscribe 256 CUs several times, but at least a few tiles
+        // per wave so the software pipeline has something to overlap
+        const int64_t target_wgs = retrieval ? 1024 : 3072;
+        const int64_t min_tps = retrieval ? 128 : 512;
+        tps = (kv_len_all * BH + target_wgs - 1) / target_wgs;
+        tps = ((tps + 63) / 64) * 64;
+        if (tps < min_tps) tps = min_tps;
+    }
+    int64_t ns = (kv_len_all + tps - 1) / tps;
+    if (ns < 1) ns = 1;
+    return SplitPlan{(int)ns, (int)tps};
+}
+
+static size_t attn_ws_bytes(int64_t BH, const SplitPlan &sp) {
+    return (size_t)BH * sp.nsplit * (kGPad * kHeadDim + 2 * kGPad) * sizeof(float);
+}
+
+size_t attn_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G, bool retrieval) {
+    if (batch <= 0 || heads <= 0 || kv_len_all <= 0 || G <= 0) return 0;
+    const int64_t BH = (int64_t)batch * heads;
+    return attn_ws_bytes(BH, plan_splits(BH, kv_len_all, retrieval));
+}
+
+int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
+                int64_t kv_len_all, int32_t G, float scale, int32_t causal, float *O, float *LSE, void *ws,
+                size_t ws_bytes, void *stream, bool retrieval) {
+    if (!Q || !K || !V || !O) return TF_ERR_INVALID_ARG;
+    int rc = check_desc(kd);
+    if (rc != TF_OK) return rc;
+    if (G < 1) return TF_ERR_INVALID_ARG;
+    if (G > TF_MAX_QUERIES) return TF_ERR_UNSUPPORTED;
+    if (kv_len_all < 1 || kv_len_all > kd->capacity) return TF_ERR_INVALID_ARG;
+    if (kd->capacity > (int64_t)1 << 30 || kd->stride_t > (1 << 24)) return TF_ERR_UNSUPPORTED;
+    if (causal && kv_len_all < G) return TF_ERR_INVALID_ARG;
+    if (!(scale == scale) || scale - scale != 0.f) return TF_ERR_INVALID_ARG;  // NaN or infinite
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return TF_ERR_INVALID_ARG;
+    const int64_t BH = (int64_t)kd->batch * kd->heads;
+    const SplitPlan sp = plan_splits(BH, kv_len_all, retrieval);
+    if (BH * sp.nsplit >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
+    if (!ws || !aligned(ws, 256) || ws_bytes < attn_ws_bytes(BH, sp)) return TF_ERR_WORKSPACE;
+
+    AttnParams p;
+    p.Q = static_cast<const uint16_t *>(Q);
+    p.K = static_cast<const uint16_t *>(K);
+    p.V = static_cast<const uint16_t *>(V);
+    p.sb = kd->stride_b;
+    p.sh = kd->stride_h;
+    p.st = kd->stride_t;
+    p.kv_len = kv_len;
+    p.kv_len_all = (int32_t)kv_len_all;
+    p.H = kd->heads;
+    p.G = G;
+    p.causal = causal ? 1 : 0;
+    p.nsplit = sp.nsplit;
+    p.tokens_per_split = sp.tokens_per_split;
+    p.scale_log2 = scale * kLog2e;
+    p.part_o = static_cast<float *>(ws);
+    p.part_ml = p.part_o + (size_t)BH * sp.nsplit * kGPad * kHeadDim;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(attn_split_kernel, dim3((unsigned)(BH * sp.nsplit)), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(BH * G)), dim3(128), 0, st, p.part_o, p.part_ml,
+                       sp.nsplit, G, O, LSE);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace tf

@@ -1,0 +1,44 @@
+// Shared host/device helpers of the gfx950 library (wave64, MFMA, LDS).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "triforce.h"
+
+namespace tf {
+
+constexpr int kHeadDim = TF_HEAD_DIM;  // 128 bf16 = 256 B per K/V row
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// 16-byte global load / store (rows are 16-byte aligned by contract)
+__device__ __forceinline__ uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
+__device__ __forceinline__ void st16(void *p, uint4 v) { *reinterpret_cast<uint4 *>(p) = v; }
+
+__device__ __forceinline__ float wave_max_xor(float v, int mask) {
+    return fmaxf(v, __shfl_xor(v, mask, kWave));
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? TF_OK : TF_ERR_HIP; }
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// validates the parts of a descriptor every call relies on
+inline int check_desc(const tf_kv_desc *d) {
+    if (!d) return TF_ERR_INVALID_ARG;
+    if (d->batch <= 0 || d->heads <= 0 || d->capacity <= 0) return TF_ERR_INVALID_ARG;
+    if (d->head_dim != kHeadDim) return TF_ERR_UNSUPPORTED;
+    if (d->stride_t < kHeadDim || d->stride_b < 0 || d->stride_h < 0) return TF_ERR_INVALID_ARG;
+    if ((d->stride_t % 8) || (d->stride_h % 8) || (d->stride_b % 8)) return TF_ERR_INVALID_ARG;
+    return TF_OK;
+}
+
+}  // namespace tf

@@ -1,0 +1,97 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, sizes its
+workspaces sanely and rejects bad arguments on the host (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2404_11912_amd as tf
+from paper_2404_11912_amd.binding import tf_kv_desc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "triforce.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(tf.LIB_PATH):
+        from paper_2404_11912_amd.build import build_library
+        build_library()
+    return tf.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tf_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(tf.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert tf.tf_version() >= 100
+    for code in (0, -1, -2, -3, -4, -99):
+        assert lib.tf_status_string(code)
+
+
+def test_workspace_queries(lib):
+    full = tf.tf_decode_attn_full_workspace_bytes(1, 32, 131072, 5)
+    retr = tf.tf_decode_attn_retrieval_workspace_bytes(1, 32, 4096, 3)
+    assert 0 < retr < full < 64 << 20                  # partials stay far below the 2 GiB of KV per layer
+    assert tf.tf_chunk_topk_gather_workspace_bytes(1, 32, 16384, 512) >= 32 * 16384 * 4
+    assert tf.tf_spec_accept_workspace_bytes(4, 5, 32000) == 4 * 9 * 16
+    assert tf.tf_decode_attn_full_workspace_bytes(0, 32, 10, 1) == 0
+
+
+def test_options(lib):
+    tf.tf_set_option("attn_full_tokens_per_split", 256)
+    small = tf.tf_decode_attn_full_workspace_bytes(1, 1, 4096, 4)
+    tf.tf_set_option("attn_full_tokens_per_split", 0)
+    assert small == 16 * (8 * 128 + 16) * 4
+    with pytest.raises(tf.TfError):
+        tf.tf_set_option("attn_full_tokens_per_split", 100)      # not a multiple of 64
+    with pytest.raises(tf.TfError):
+        tf.tf_set_option("no_such_option", 1)
+
+
+def test_host_side_argument_checks(lib):
+    """Every call validates on the host and returns before touching the GPU."""
+    d = tf_kv_desc(1, 2, 128, 0, 64, 2 * 64 * 128, 64 * 128, 128)
+    bad_dim = tf_kv_desc(1, 2, 64, 0, 64, 2 * 64 * 64, 64 * 64, 64)
+    p = ctypes.c_void_p(4096)          # never dereferenced on the host
+    ref = ctypes.byref
+    # null pointers
+    assert lib.tf_decode_attn_full(None, p, p, ref(d), None, 64, 4, 1.0, 1, p, None, p, 1 << 20, None) == -1
+    assert lib.tf_chunk_summarize(None, ref(d), 8, 0, 8, p, 8, None) == -1
+    assert lib.tf_spec_accept(None, p, p, 1, 2, 10, 1.0, p, p, p, p, p, 1 << 10, None) == -1
+    # unsupported shapes
+    assert lib.tf_decode_attn_full(p, p, p, ref(bad_dim), None, 64, 4, 1.0, 1, p, None, p, 1 << 20, None) == -2
+    assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 64, 9, 1.0, 1, p, None, p, 1 << 20, None) == -2
+    assert lib.tf_chunk_topk_gather(p, p, 8, p, p, ref(d), 8, None, 8, 4096, p, None, None, None, None,
+                                    p, 1 << 20, None) == -2
+    # inconsistent sizes
+    assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 65, 4, 1.0, 1, p, None, p, 1 << 20, None) == -1
+    assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 3, 4, 1.0, 1, p, None, p, 1 << 20, None) == -1
+    assert lib.tf_chunk_summarize(p, ref(d), 8, 0, 9, p, 16, None) == -1       # 9 chunks of 8 > capacity 64
+    assert lib.tf_chunk_topk_gather(p, p, 8, p, p, ref(d), 8, None, 8, 9, p, None, None, None, None,
+                                    p, 1 << 20, None) == -1                    # k > n_chunks
+    assert lib.tf_spec_accept(p, p, p, 1, 2, 10, -1.0, p, p, p, p, p, 1 << 10, None) == -1
+    # workspace too small / missing
+    assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 64, 4, 1.0, 1, p, None, p, 16, None) == -3
+    assert lib.tf_decode_attn_retrieval(p, p, p, ref(d), None, 64, 4, 1.0, 1, p, None, None, 0, None) == -3
+    assert lib.tf_spec_accept(p, p, p, 1, 2, 10, 1.0, p, p, p, p, p, 8, None) == -3
+    # empty range is a no-op that succeeds
+    assert lib.tf_chunk_summarize(p, ref(d), 8, 0, 0, p, 8, None) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 1, 16, 128, dtype=torch.bfloat16)
+    with pytest.raises(TypeError):
+        tf.kv_desc(x)
