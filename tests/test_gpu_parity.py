@@ -258,7 +258,7 @@ def test_topk_exact_ties_go_to_lower_index():
     rng = np.random.default_rng(121)
     B, H, M, k = 1, 2, 300, 40
     base = rng.standard_normal((B, H, 20, 128)).astype(np.float32)
-    km = base[:, :, rng.integers(0, 20, M), :]                     # 300 rows drawn from 20 distinct ones
+    km = np.ascontiguousarray(base[:, :, rng.integers(0, 20, M), :])      # 300 rows drawn from 20 distinct ones
     q = bf16_u16(rng.standard_normal((B, H, 128)) * 0.3)
     x = {"K": torch.zeros(B, H, M, 128, dtype=torch.bfloat16), "V": torch.zeros(B, H, M, 128, dtype=torch.bfloat16),
          "q_r": u16_torch(q)}
