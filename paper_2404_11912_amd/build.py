@@ -20,6 +20,7 @@ SOURCES = ["tf_api.hip", "tf_attn.hip", "tf_summarize.hip", "tf_topk_gather.hip"
 # packed-fp32 instructions are switched off for all device code of this library
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA accumulators stay in ordinary VGPRs
              "-Wno-unused-command-line-argument"]
 
 

@@ -63,13 +63,19 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) v_off[i] = (uint32_t)((4 * s + i) * row_bytes + r * 16);
 
-    // resident Q operand: lane (r,s) holds Q[query r][32kk + 8s .. +8], zero for r >= G
-    uint4 qb[4];
+    // Q operand of the QK^T MFMAs, kept in LDS (re-read per tile: 4 KiB per tile is nothing for
+    // LDS, and 16 VGPRs fewer per lane buy a third wave per SIMD): entry [kk][lane] holds
+    // Q[query r][32kk + 8s .. +8] for lane (r,s), zero for r >= G
+    __shared__ uint4 sm_q[4][kWave];
+    if (wave == 0) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        qb[kk] = make_uint4(0, 0, 0, 0);
-        if (r < p.G) qb[kk] = ld16(p.Q + ((int64_t)bh * p.G + r) * kHeadDim + kk * 32 + s * 8);
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4 qv = make_uint4(0, 0, 0, 0);
+            if (r < p.G) qv = ld16(p.Q + ((int64_t)bh * p.G + r) * kHeadDim + kk * 32 + s * 8);
+            sm_q[kk][lane] = qv;
+        }
     }
+    __syncthreads();
 
     // tokens < n_all are visible to every query; this lane's query sees tokens < n_mine
     const int n_all = p.causal ? len - p.G + 1 : len;
@@ -94,6 +100,10 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     // S^T tile: four bf16 MFMAs over the head dim, then the log2-domain scale
     auto qk_tile = [&](const uint4(&k)[4], float(&z)[4]) {
         f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        asm volatile("" ::: "memory");  // keep the Q reads inside the loop (not hoisted into registers)
+        uint4 qb[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) qb[kk] = sm_q[kk][lane];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
             sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k[kk]),
@@ -242,26 +252,81 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     }
 }
 
-// merge the split partials of one (b,h,g): one 128-thread block, thread = output dim
-__global__ __launch_bounds__(128) void attn_combine_kernel(const float *__restrict__ part_o,
-                                                           const float *__restrict__ part_ml,
-                                                           int nsplit, int G, float *__restrict__ O,
-                                                           float *__restrict__ LSE) {
+// Merge the split partials of one (b,h,g). 512 threads = 4 groups x 128 output dims. The
+// per-split maxima and sums are staged in LDS, turned into weights once, and each group
+// accumulates every 4th split with independent loads in flight; groups are summed in LDS.
+constexpr int kCombineThreads = 512;
+constexpr int kCombineGroups = kCombineThreads / kHeadDim;
+constexpr int kMaxSplits = 2048;
+
+__global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const float *__restrict__ part_o,
+                                                                       const float *__restrict__ part_ml,
+                                                                       int nsplit, int G, float *__restrict__ O,
+                                                                       float *__restrict__ LSE) {
+    __shared__ float sm_w[kMaxSplits];   // running max, then weight exp2(m - M), per split
+    __shared__ float sm_l[kMaxSplits];
+    __shared__ float sm_red[kCombineThreads / 64];
+    __shared__ float sm_acc[kCombineGroups][kHeadDim];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bh = blockIdx.x / G, g = blockIdx.x - bh * G;
-    const int dim = threadIdx.x;
     const int64_t base = (int64_t)bh * nsplit;
-    float M = -INFINITY;
-    for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, part_ml[((base + sp) * 2 + 0) * kGPad + g]);
-    const float Ms = safe_max(M);
-    float L = 0.f, acc = 0.f;
-    for (int sp = 0; sp < nsplit; ++sp) {
-        const float a = __builtin_amdgcn_exp2f(part_ml[((base + sp) * 2 + 0) * kGPad + g] - Ms);
-        L += a * part_ml[((base + sp) * 2 + 1) * kGPad + g];
-        acc += a * part_o[((base + sp) * kGPad + g) * kHeadDim + dim];
+
+    float mx = -INFINITY;
+    for (int sp = tid; sp < nsplit; sp += kCombineThreads) {
+        const float m = part_ml[((base + sp) * 2 + 0) * kGPad + g];
+        sm_w[sp] = m;
+        sm_l[sp] = part_ml[((base + sp) * 2 + 1) * kGPad + g];
+        mx = fmaxf(mx, m);
     }
-    const int64_t row = (int64_t)bh * G + g;
-    O[row * kHeadDim + dim] = L > 0.f ? acc / L : 0.f;
-    if (LSE && dim == 0) LSE[row] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = wave_max_xor(mx, off);
+    if (lane == 0) sm_red[wave] = mx;
+    __syncthreads();
+    float M = sm_red[0];
+#pragma unroll
+    for (int w = 1; w < kCombineThreads / 64; ++w) M = fmaxf(M, sm_red[w]);
+    const float Ms = safe_max(M);
+    float lpart = 0.f;
+    for (int sp = tid; sp < nsplit; sp += kCombineThreads) {
+        const float a = __builtin_amdgcn_exp2f(sm_w[sp] - Ms);
+        sm_w[sp] = a;
+        lpart += a * sm_l[sp];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) lpart += __shfl_xor(lpart, off, kWave);
+    __syncthreads();  // sm_red is reused; weights become visible
+    if (lane == 0) sm_red[wave] = lpart;
+    __syncthreads();
+    float L = 0.f;
+#pragma unroll
+    for (int w = 0; w < kCombineThreads / 64; ++w) L += sm_red[w];
+
+    const int dim = tid & (kHeadDim - 1), grp = tid >> 7;
+    const float *po = part_o + (base * kGPad + g) * kHeadDim + dim;
+    constexpr int64_t split_stride = (int64_t)kGPad * kHeadDim;
+    float acc = 0.f;
+    int sp = grp;
+    for (; sp + 3 * kCombineGroups < nsplit; sp += 4 * kCombineGroups) {
+        const float v0 = po[(int64_t)sp * split_stride];
+        const float v1 = po[(int64_t)(sp + kCombineGroups) * split_stride];
+        const float v2 = po[(int64_t)(sp + 2 * kCombineGroups) * split_stride];
+        const float v3 = po[(int64_t)(sp + 3 * kCombineGroups) * split_stride];
+        acc += sm_w[sp] * v0;
+        acc += sm_w[sp + kCombineGroups] * v1;
+        acc += sm_w[sp + 2 * kCombineGroups] * v2;
+        acc += sm_w[sp + 3 * kCombineGroups] * v3;
+    }
+    for (; sp < nsplit; sp += kCombineGroups) acc += sm_w[sp] * po[(int64_t)sp * split_stride];
+    sm_acc[grp][dim] = acc;
+    __syncthreads();
+    if (tid < kHeadDim) {
+        float tot = sm_acc[0][tid];
+#pragma unroll
+        for (int q = 1; q < kCombineGroups; ++q) tot += sm_acc[q][tid];
+        const int64_t row = (int64_t)bh * G + g;
+        O[row * kHeadDim + tid] = L > 0.f ? tot / L : 0.f;
+        if (LSE && tid == 0) LSE[row] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+    }
 }
 
 struct SplitPlan {
@@ -277,18 +342,37 @@ int set_attn_option(bool retrieval, int64_t v) {
     return TF_OK;
 }
 
+// compute units of the current device (256 on a full MI355X), queried once
+static int num_cus() {
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cached = n;
+        else
+            cached = 256;
+    }
+    return cached;
+}
+
 static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, bool retrieval) {
     int64_t tps = retrieval ? g_tps_retr : g_tps_full;
     if (tps == 0) {
-        // enough workgroups to oversubscribe 256 CUs several times, but at least a few tiles
-        // per wave so the software pipeline has something to overlap
-        const int64_t target_wgs = retrieval ? 1024 : 3072;
+        // The split kernel fits 3 workgroups (12 waves) per CU. Long caches: exactly one
+        // resident round of equal workgroups (measured best at 128K context: no tail, few
+        // partials). Short caches: more, smaller workgroups, but at least 128 tokens each.
+        const int64_t target_wgs = (int64_t)num_cus() * 3;
         const int64_t min_tps = retrieval ? 128 : 512;
         tps = (kv_len_all * BH + target_wgs - 1) / target_wgs;
         tps = ((tps + 63) / 64) * 64;
         if (tps < min_tps) tps = min_tps;
     }
     int64_t ns = (kv_len_all + tps - 1) / tps;
+    if (ns > kMaxSplits) {  // the merge kernel stages one weight per split in LDS
+        tps = (((kv_len_all + kMaxSplits - 1) / kMaxSplits + 63) / 64) * 64;
+        ns = (kv_len_all + tps - 1) / tps;
+    }
     if (ns < 1) ns = 1;
     return SplitPlan{(int)ns, (int)tps};
 }
@@ -341,7 +425,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(attn_split_kernel, dim3((unsigned)(BH * sp.nsplit)), dim3(256), 0, st, p);
-    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(BH * G)), dim3(128), 0, st, p.part_o, p.part_ml,
+    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(BH * G)), dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
                        sp.nsplit, G, O, LSE);
     return hip_status(hipGetLastError());
 }
