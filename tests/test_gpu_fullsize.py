@@ -1,0 +1,134 @@
+"""GPU parity at the full per-layer sizes of the specified workloads, in the launch configuration
+bench.py times (default split planning, one layer = all batch x head units). Inputs are drawn by
+the seeded device generator; a sample of (batch, head) units is copied to the host and the oracle
+computes their outputs one by one. Properties that hold at any size are checked on every unit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_11912_amd as tf
+from paper_2404_11912_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+ATTN_TOL, LSE_TOL, TIE_BAND = 2e-3, 1e-3, 1e-4
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _unit(t, b, h):
+    """One (b,h) unit of a device tensor as a host uint16 / numpy array with unit batch and head dims."""
+    x = t[b:b + 1, h:h + 1].contiguous()
+    return synth.as_u16(x) if x.dtype == torch.bfloat16 else x.cpu().numpy()
+
+
+@pytest.mark.parametrize("name,units", [
+    ("step128k", [(0, 0), (0, 13), (0, 31)]),
+    ("batch4x64k", [(0, 5), (2, 17), (3, 31)]),
+    ("extreme1m", [(0, 7), (0, 30)]),
+])
+def test_one_layer_at_full_size(name, units):
+    w = synth.WORKLOADS[name]
+    layer = 1
+    say(f"case fullsize {name} layer={layer} seed={synth.seed_for(w, layer)} units={units}")
+    x = synth.make_workload_layer(w, layer, DEV)
+    K, V, Q, q_r = x["K"], x["V"], x["Q"], x["q_r"]
+    B, H, N, d = K.shape
+
+    # whole path on the device, default launch configuration
+    Kmean = torch.empty((B, H, w.M, d), dtype=torch.float32, device=DEV)
+    tf.tf_chunk_summarize(K, w.c, Kmean, 0, w.M)
+    idx = torch.empty((B, H, w.k), dtype=torch.int32, device=DEV)
+    score = torch.empty((B, H, w.k), dtype=torch.float32, device=DEV)
+    Kr = torch.zeros((B, H, w.R, d), dtype=torch.bfloat16, device=DEV)
+    Vr = torch.zeros_like(Kr)
+    tf.tf_chunk_topk_gather(q_r, Kmean, K, V, w.c, w.k, idx, Kr, Vr, out_score=score)
+    Qd = Q[:, :, -w.G_d:, :].contiguous()
+    O_d = torch.empty(Qd.shape, dtype=torch.float32, device=DEV)
+    L_d = torch.empty(Qd.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_retrieval(Qd, Kr, Vr, O_d, L_d, causal=False)
+    O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+    L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_full(Q, K, V, O, L, causal=True)
+    torch.cuda.synchronize()
+    say(f"[{name}] device path done")
+
+    # properties on every unit ------------------------------------------------------------
+    idx_h = idx.cpu().numpy()
+    assert idx_h.min() >= 0 and idx_h.max() < w.M
+    srt = np.sort(idx_h, axis=-1)
+    assert np.all(srt[..., 1:] > srt[..., :-1])                       # distinct
+    sc_h = score.cpu().numpy()
+    assert np.all(sc_h[..., 1:] <= sc_h[..., :-1])                    # descending importance
+    planted = x["planted"].cpu().numpy()
+    for b in range(B):
+        for h in range(H):
+            assert set(planted[b, h].tolist()) <= set(idx_h[b, h].tolist())
+    if w.P == w.k:                                                     # budget == planted chunks
+        assert np.array_equal(srt, np.sort(planted, axis=-1))
+    # gathered rows are bit-exact copies of the rows the indices name (checked on the device)
+    rows = (idx.long()[..., None] * w.c + torch.arange(w.c, device=DEV)).reshape(B, H, w.k * w.c)
+    gi = rows[..., None].expand(B, H, w.k * w.c, d)
+    assert torch.equal(Kr.view(torch.int16), torch.gather(K, 2, gi).view(torch.int16))
+    assert torch.equal(Vr.view(torch.int16), torch.gather(V, 2, gi).view(torch.int16))
+    assert torch.isfinite(O).all() and torch.isfinite(L).all() and torch.isfinite(O_d).all()
+    del gi, rows
+
+    # sampled units against the oracle ----------------------------------------------------
+    for (b, h) in units:
+        Ku, Vu, Qu = _unit(K, b, h), _unit(V, b, h), _unit(Q, b, h)
+        km = oracle.chunk_mean(Ku, w.c)
+        got_km = Kmean[b, h].cpu().numpy().astype(np.float64)
+        assert np.max(np.abs(got_km - km[0, 0])) < 2e-7 * max(1.0, np.abs(km).max())
+        o_scores, o_idx = oracle.retrieve(_unit(q_r, b, h)[:, :, :], km, w.k)
+        s = o_scores[0, 0]
+        got = idx_h[b, h]
+        tau = s[o_idx[0, 0, -1]]
+        assert set(np.where(s > tau + TIE_BAND)[0].tolist()) <= set(got.tolist())
+        assert not (set(got.tolist()) & set(np.where(s < tau - TIE_BAND)[0].tolist()))
+        along = s[got]
+        assert np.all(along[1:] <= along[:-1] + TIE_BAND)
+        assert np.max(np.abs(sc_h[b, h] - along)) < 2e-5 * max(1.0, np.abs(along).max())
+        same_set = set(got.tolist()) == set(o_idx[0, 0].tolist())
+        # verification attention over the full cache
+        Oo, Lo, _ = oracle.attention(Qu, Ku, Vu, scale=1.0, causal=True)
+        e = float(np.max(np.abs(O[b, h].cpu().numpy() - Oo[0, 0])))
+        el = float(np.max(np.abs(L[b, h].cpu().numpy() - Lo[0, 0])))
+        # draft attention over the retrieval cache (comparable when the selected set is unique)
+        ed = float("nan")
+        if same_set:
+            oKr, oVr = oracle.gather(Ku, Vu, o_idx, w.c)
+            Od, Ld, _ = oracle.attention(np.ascontiguousarray(Qu[:, :, -w.G_d:, :]), oKr, oVr, scale=1.0,
+                                         causal=False)
+            ed = float(np.max(np.abs(O_d[b, h].cpu().numpy() - Od[0, 0])))
+            assert ed <= ATTN_TOL
+            assert np.max(np.abs(L_d[b, h].cpu().numpy() - Ld[0, 0])) <= LSE_TOL
+        say(f"[{name}] unit {(b, h)}: verify max|dO|={e:.2e} max|dLSE|={el:.2e}; "
+            f"same chunk set={same_set}; draft max|dO|={ed:.2e}")
+        assert e <= ATTN_TOL and el <= LSE_TOL
+
+
+@pytest.mark.parametrize("gamma", [2, 4, 6])
+def test_accept_batch4_vocab_32000(gamma):
+    """Batched accept of the batch-4 workload: per-sequence seeds, gamma in {2,4,6}, T = 0.6."""
+    w = synth.WORKLOADS["batch4x64k"]
+    say(f"case fullsize accept gamma={gamma}")
+    parts = [synth.make_accept_inputs(1, gamma, w.V, 0.6, synth.seed_for(w, 0, b) + 7, correlated=(b % 2 == 0))
+             for b in range(w.B)]
+    a = {k: torch.cat([p[k] for p in parts], 0) for k in parts[0] if torch.is_tensor(parts[0][k])}
+    Tf = float(np.float32(0.6))
+    n_o, out_o, ma, ms = oracle.accept(a["target_logits"].numpy(), a["draft_logits"].numpy(),
+                                       a["draft_tokens"].numpy(), Tf, a["u_accept"].numpy(), a["u_sample"].numpy())
+    n = torch.empty((w.B,), dtype=torch.int32, device=DEV)
+    out = torch.empty((w.B, gamma + 1), dtype=torch.int32, device=DEV)
+    tf.tf_spec_accept(a["target_logits"].to(DEV), a["draft_logits"].to(DEV), a["draft_tokens"].to(DEV), 0.6,
+                      a["u_accept"].to(DEV), a["u_sample"].to(DEV), n, out)
+    torch.cuda.synchronize()
+    safe = (ma > 1e-9) & (ms > 1e-9)
+    assert safe.all()
+    assert np.array_equal(n.cpu().numpy(), n_o) and np.array_equal(out.cpu().numpy(), out_o)
