@@ -14,6 +14,9 @@
  *                                                                      (Algorithm 1, M_p(C_r,..))
  *   tf_spec_accept            Verify / Correct / bonus token: lossless speculative sampling
  *                                                                      (Algorithm 1, Sec. 4.2)
+ * and, beyond those five, the cache-update pieces of Sec. 4.3:
+ *   tf_decode_attn_indexed    drafting through the chunk indices, no gathered copy
+ *   tf_kv_append              write new tokens' K/V rows into a cache
  *
  * Conventions (all calls)
  *   - Every data pointer is a DEVICE pointer owned by the caller (the only host pointers are
@@ -147,6 +150,47 @@ int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const 
                              const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
                              int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes,
                              void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_decode_attn_indexed -- gather-free drafting (Algorithm 1, "Run M_p with retrieval cache
+ * C_r"; Sec. 4.1 chunk selection): the same attention, over a draft cache that is never
+ * materialised. For every (b,h) the draft cache is the concatenation of
+ *   (1) the chunks idx[b,h,0..k_chunks) of the cache (K,V,kd): chunk j contributes the rows
+ *       idx[b,h,j]*chunk .. idx[b,h,j]*chunk+chunk-1; negative entries (and chunks reaching
+ *       beyond kv_len_all) are skipped; and
+ *   (2) the recent rows [rb[b], len[b]) of the same cache, rb[b] = recent_begin ?
+ *       recent_begin[b] : recent_begin_all (recent_begin_all is always a lower bound of
+ *       rb[b]); these are the tokens appended since idx was built, the G queries' own
+ *       tokens last.
+ * Causal masking is bottom-right aligned on that virtual sequence: its last G tokens are the
+ * queries, so causal != 0 requires at least G recent rows (len[b] - rb[b] >= G). With idx from tf_chunk_topk_gather this equals tf_decode_attn_retrieval over the
+ * gathered cache followed by the same recent rows, without the copy. idx is int32
+ * [batch, heads, k_chunks]; the caller keeps selected chunks and the recent range disjoint.
+ * Other arguments as in tf_decode_attn_full. k_chunks >= 0; chunk in [1, 64];
+ * workspace: pass an upper bound of len[b]-rb[b] as recent_len_all.
+ * ------------------------------------------------------------------------------------- */
+size_t tf_decode_attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chunks,
+                                              int32_t chunk, int64_t recent_len_all, int32_t G);
+int tf_decode_attn_indexed(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                           const int32_t *idx, int32_t k_chunks, int32_t chunk,
+                           const int32_t *kv_len, int64_t kv_len_all, const int32_t *recent_begin,
+                           int64_t recent_begin_all, int32_t G, float scale, int32_t causal, float *O,
+                           float *LSE, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_kv_append -- cache update of Algorithm 1 ("Update C_r, C_q based on the accepted
+ * tokens"; Sec. 4.3: new tokens overwrite the least important entries of the retrieval cache).
+ *   K[b,h,p[b]+i,:] = Knew[b,h,i,:] (same for V) for i < n, p[b] = pos ? pos[b] : pos_all.
+ *   Knew, Vnew in  bf16 [batch, heads, n, 128] contiguous
+ *   K, V       out bf16, described by kd; bit-exact row copies; other rows untouched
+ *   pos        in  int32 [batch] device array, or NULL
+ * Destination rows outside [0, capacity) are dropped (only possible with a device `pos`).
+ * Appending to the full cache uses p = current length; committing accepted tokens to a
+ * retrieval cache of budget R that already holds m committed tokens uses p = R - m - n (the
+ * tail of the descending-importance order).
+ * ------------------------------------------------------------------------------------- */
+int tf_kv_append(const void *Knew, const void *Vnew, int32_t n, void *K, void *V,
+                 const tf_kv_desc *kd, const int32_t *pos, int64_t pos_all, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * tf_spec_accept -- Algorithm 1, Verify / Correct / "sample next token" lines, i.e. the

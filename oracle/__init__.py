@@ -6,9 +6,11 @@ this package. It never imports the HIP package and shares no code with it.
 from .tf_oracle import (  # noqa: F401
     accept,
     attention,
+    attention_indexed,
     build_oracle,
     chunk_mean,
     gather,
+    kv_append,
     num_threads,
     retrieve,
 )

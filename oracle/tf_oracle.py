@@ -144,3 +144,52 @@ def accept(target_logits, draft_logits, draft_tokens, temperature: float, u_acce
     if rc != 0:
         raise ValueError("orc_accept: bad argument")
     return n_acc, out, ma, ms
+
+
+def attention_indexed(Q, K, V, idx, c: int, kv_len=None, recent_begin=None, scale: float = 1.0,
+                      causal: bool = True, kv_len_all: int | None = None):
+    """Gather-free drafting, written as its definition (Algorithm 1, M_p(C_r, ...); Sec. 4.1): for
+    every (b,h) build the draft cache explicitly -- the rows of chunks idx[b,h,:] in that order
+    (chunk m = rows m*c .. m*c+c-1; negative entries and chunks reaching beyond kv_len_all are
+    skipped), then the recent rows [recent_begin[b], kv_len[b]) -- and run the plain attention
+    over it (causal mask bottom-right aligned on the concatenation; the G queries' own rows are
+    the last recent rows, so causal needs at least G recent rows).
+    Q [B,H,G,d], K,V [B,H,N,d] uint16(bf16), idx int [B,H,k] -> (O, LSE) float64."""
+    Q, K, V = _u16(Q), _u16(K), _u16(V)
+    idx = np.asarray(idx)
+    B, H, G, d = Q.shape
+    N = K.shape[2]
+    kv_len_all = N if kv_len_all is None else int(kv_len_all)
+    kv = np.broadcast_to(np.asarray(kv_len_all if kv_len is None else kv_len, dtype=np.int64), (B,))
+    rb = np.broadcast_to(np.asarray(kv if recent_begin is None else recent_begin, dtype=np.int64), (B,))
+    O = np.zeros((B, H, G, d), dtype=np.float64)
+    LSE = np.full((B, H, G), -np.inf, dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            rows = [np.arange(m * c, m * c + c) for m in idx[b, h].tolist() if m >= 0 and (m + 1) * c <= kv_len_all]
+            rows.append(np.arange(min(int(rb[b]), int(kv[b])), int(kv[b])))
+            rows = np.concatenate(rows).astype(np.int64)
+            if causal and int(kv[b]) - min(int(rb[b]), int(kv[b])) < G:
+                raise ValueError("causal indexed attention needs at least G recent rows")
+            if rows.size == 0:
+                continue
+            Kv = np.ascontiguousarray(K[b, h][rows])[None, None]
+            Vv = np.ascontiguousarray(V[b, h][rows])[None, None]
+            o, l, _ = attention(Q[b:b + 1, h:h + 1], Kv, Vv, scale=scale, causal=causal)
+            O[b, h], LSE[b, h] = o[0, 0], l[0, 0]
+    return O, LSE
+
+
+def kv_append(Knew, Vnew, K, V, pos):
+    """Cache update (Algorithm 1, "Update C_r, C_q"; Sec. 4.3): returns copies of K, V with
+    K[b,h,pos[b]+i] = Knew[b,h,i] (same for V); destination rows outside the cache are dropped."""
+    Knew, Vnew, K, V = _u16(Knew), _u16(Vnew), _u16(K).copy(), _u16(V).copy()
+    B, H, n, d = Knew.shape
+    pos = np.broadcast_to(np.asarray(pos, dtype=np.int64), (B,))
+    for b in range(B):
+        for i in range(n):
+            t = int(pos[b]) + i
+            if 0 <= t < K.shape[2]:
+                K[b, :, t] = Knew[b, :, i]
+                V[b, :, t] = Vnew[b, :, i]
+    return K, V

@@ -17,6 +17,9 @@ from .binding import (  # noqa: F401
     tf_chunk_topk_gather,
     tf_chunk_topk_gather_workspace_bytes,
     tf_decode_attn_full,
+    tf_decode_attn_indexed,
+    tf_decode_attn_indexed_workspace_bytes,
+    tf_kv_append,
     tf_decode_attn_full_workspace_bytes,
     tf_decode_attn_retrieval,
     tf_decode_attn_retrieval_workspace_bytes,

@@ -26,6 +26,7 @@ EXPORTS = (
     "tf_decode_attn_full_workspace_bytes", "tf_decode_attn_full",
     "tf_decode_attn_retrieval_workspace_bytes", "tf_decode_attn_retrieval",
     "tf_spec_accept_workspace_bytes", "tf_spec_accept",
+    "tf_decode_attn_indexed_workspace_bytes", "tf_decode_attn_indexed", "tf_kv_append",
 )
 
 
@@ -73,6 +74,13 @@ def load_library() -> ctypes.CDLL:
         getattr(lib, name + "_workspace_bytes").argtypes = [i32, i32, i64, i32]
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, i32, vp, vp, vp, sz, vp]
+    lib.tf_decode_attn_indexed_workspace_bytes.restype = sz
+    lib.tf_decode_attn_indexed_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i32]
+    lib.tf_decode_attn_indexed.restype = ctypes.c_int
+    lib.tf_decode_attn_indexed.argtypes = [vp, vp, vp, dp, vp, i32, i32, vp, i64, vp, i64, i32, f32, i32, vp, vp,
+                                           vp, sz, vp]
+    lib.tf_kv_append.restype = ctypes.c_int
+    lib.tf_kv_append.argtypes = [vp, vp, i32, vp, vp, dp, vp, i64, vp]
     lib.tf_spec_accept_workspace_bytes.restype = sz
     lib.tf_spec_accept_workspace_bytes.argtypes = [i32, i32, i32]
     lib.tf_spec_accept.restype = ctypes.c_int
@@ -229,6 +237,72 @@ def tf_decode_attn_retrieval(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None,
                              causal: bool = True, ws=None, stream=None):
     """Draft attention: the same operation over the retrieval cache (K, V = Kr, Vr)."""
     return _attn("tf_decode_attn_retrieval", Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream)
+
+
+def tf_decode_attn_indexed_workspace_bytes(batch: int, heads: int, k_chunks: int, chunk: int,
+                                           recent_len_all: int, G: int) -> int:
+    return int(load_library().tf_decode_attn_indexed_workspace_bytes(batch, heads, k_chunks, chunk,
+                                                                     recent_len_all, G))
+
+
+def tf_decode_attn_indexed(Q, K, V, idx, chunk: int, O, LSE=None, kv_len=None, kv_len_all=None,
+                           recent_begin=None, recent_begin_all=None, scale: float = 1.0, causal: bool = True,
+                           ws=None, stream=None):
+    """Draft attention through chunk indices: chunks idx[b,h,:] of the cache, then its rows
+    [recent_begin, len). recent_begin_all defaults to kv_len_all (no recent rows)."""
+    lib = load_library()
+    _need(Q, torch.bfloat16, "Q")
+    _need(O, torch.float32, "O")
+    _need(idx, torch.int32, "idx")
+    d = kv_desc(K)
+    kv_desc(V)
+    if V.stride() != K.stride() or V.shape != K.shape:
+        raise ValueError("K and V must share shape and strides")
+    if Q.dim() != 4 or Q.shape[0] != d.batch or Q.shape[1] != d.heads or Q.shape[3] != d.head_dim:
+        raise ValueError("Q must be [B,H,G,d]")
+    if idx.dim() != 3 or idx.shape[0] != d.batch or idx.shape[1] != d.heads:
+        raise ValueError("idx must be [B,H,k]")
+    G, k = Q.shape[2], idx.shape[2]
+    if tuple(O.shape) != tuple(Q.shape):
+        raise ValueError("O must be [B,H,G,d]")
+    if LSE is not None:
+        _need(LSE, torch.float32, "LSE")
+    if kv_len is not None:
+        _need(kv_len, torch.int32, "kv_len")
+    if recent_begin is not None:
+        _need(recent_begin, torch.int32, "recent_begin")
+    if kv_len_all is None:
+        kv_len_all = K.shape[2]
+    if recent_begin_all is None:
+        recent_begin_all = kv_len_all
+    if ws is None:
+        nbytes = lib.tf_decode_attn_indexed_workspace_bytes(d.batch, d.heads, int(k), int(chunk),
+                                                            int(kv_len_all - recent_begin_all), int(G))
+        ws = workspace(nbytes, K.device)
+    _check("tf_decode_attn_indexed",
+           lib.tf_decode_attn_indexed(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(idx), int(k), int(chunk),
+                                      _ptr(kv_len), int(kv_len_all), _ptr(recent_begin), int(recent_begin_all),
+                                      int(G), float(scale), int(bool(causal)), _ptr(O), _ptr(LSE), _ptr(ws),
+                                      ws.numel() * ws.element_size(), _stream(stream)))
+    return O
+
+
+def tf_kv_append(Knew, Vnew, K, V, pos=None, pos_all: int = 0, stream=None):
+    """K[b,h,p+i] = Knew[b,h,i] (and V) for i < n, p = pos[b] (device int32) or pos_all."""
+    lib = load_library()
+    _need(Knew, torch.bfloat16, "Knew")
+    _need(Vnew, torch.bfloat16, "Vnew")
+    d = kv_desc(K)
+    kv_desc(V)
+    if V.stride() != K.stride() or V.shape != K.shape:
+        raise ValueError("K and V must share shape and strides")
+    if Knew.dim() != 4 or tuple(Knew.shape[:2]) != (d.batch, d.heads) or Knew.shape[3] != d.head_dim \
+            or tuple(Vnew.shape) != tuple(Knew.shape):
+        raise ValueError("Knew, Vnew must be [B,H,n,d]")
+    if pos is not None:
+        _need(pos, torch.int32, "pos")
+    _check("tf_kv_append", lib.tf_kv_append(_ptr(Knew), _ptr(Vnew), int(Knew.shape[2]), _ptr(K), _ptr(V),
+                                            ctypes.byref(d), _ptr(pos), int(pos_all), _stream(stream)))
 
 
 def tf_spec_accept_workspace_bytes(B: int, G: int, V: int) -> int:

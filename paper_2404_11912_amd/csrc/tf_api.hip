@@ -11,8 +11,11 @@ int topk_gather_launch(const void *, const float *, int64_t, const void *, const
                        const int32_t *, int64_t, int32_t, int32_t *, float *, void *, void *, const tf_kv_desc *,
                        void *, size_t, void *);
 size_t attn_workspace_bytes(int32_t, int32_t, int64_t, int32_t, bool);
+size_t attn_indexed_workspace_bytes(int32_t, int32_t, int32_t, int32_t, int64_t, int32_t);
 int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, const int32_t *, int64_t, int32_t,
-                float, int32_t, float *, float *, void *, size_t, void *, bool);
+                float, int32_t, float *, float *, void *, size_t, void *, bool, const IndexedArgs *);
+int kv_append_launch(const void *, const void *, int32_t, void *, void *, const tf_kv_desc *, const int32_t *,
+                     int64_t, void *);
 int set_attn_option(bool retrieval, int64_t v);
 size_t accept_workspace_bytes(int32_t, int32_t, int32_t);
 int accept_launch(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, float, const float *,
@@ -65,7 +68,7 @@ size_t tf_decode_attn_full_workspace_bytes(int32_t batch, int32_t heads, int64_t
 int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
                         int64_t kv_len_all, int32_t G, float scale, int32_t causal, float *O, float *LSE, void *ws,
                         size_t ws_bytes, void *stream) {
-    return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, false);
+    return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, false, nullptr);
 }
 
 size_t tf_decode_attn_retrieval_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G) {
@@ -75,7 +78,26 @@ size_t tf_decode_attn_retrieval_workspace_bytes(int32_t batch, int32_t heads, in
 int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
                              const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale, int32_t causal,
                              float *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
-    return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, true);
+    return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, true, nullptr);
+}
+
+size_t tf_decode_attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chunks, int32_t chunk,
+                                              int64_t recent_len_all, int32_t G) {
+    return tf::attn_indexed_workspace_bytes(batch, heads, k_chunks, chunk, recent_len_all, G);
+}
+
+int tf_decode_attn_indexed(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *idx,
+                           int32_t k_chunks, int32_t chunk, const int32_t *kv_len, int64_t kv_len_all,
+                           const int32_t *recent_begin, int64_t recent_begin_all, int32_t G, float scale,
+                           int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
+    const tf::IndexedArgs ix{idx, k_chunks, chunk, recent_begin, recent_begin_all};
+    return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, true,
+                           &ix);
+}
+
+int tf_kv_append(const void *Knew, const void *Vnew, int32_t n, void *K, void *V, const tf_kv_desc *kd,
+                 const int32_t *pos, int64_t pos_all, void *stream) {
+    return tf::kv_append_launch(Knew, Vnew, n, K, V, kd, pos, pos_all, stream);
 }
 
 size_t tf_spec_accept_workspace_bytes(int32_t B, int32_t G, int32_t V) {

@@ -28,16 +28,25 @@ struct AttnParams {
     const uint16_t *Q, *K, *V;
     int64_t sb, sh, st;
     const int32_t *kv_len;
-    int32_t kv_len_all;
+    int32_t kv_len_all;  // plain: upper bound of the cache length; indexed: of the virtual length
     int32_t H, G, causal;
     int32_t nsplit, tokens_per_split;
     float scale_log2;
     float *part_o;   // [BH][nsplit][kGPad][128]
     float *part_ml;  // [BH][nsplit][2][kGPad]   (running max in log2 units, then sum)
+    // indexed mode only: the virtual sequence of (b,h) is the chunks idx[b,h,0..k_chunks) of the
+    // cache (chunk j = rows idx*chunk .. idx*chunk+chunk-1, negative entries skipped) followed
+    // by the cache rows [recent_begin, len)
+    const int32_t *idx;
+    int32_t k_chunks, chunk;
+    const int32_t *recent_begin;
+    int32_t recent_begin_all;
+    int32_t full_len_all;  // upper bound of the real cache length (rows that may be read)
 };
 
 __device__ __forceinline__ float safe_max(float m) { return m == -INFINITY ? 0.0f : m; }
 
+template <bool kIndexed>
 __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -47,8 +56,19 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     const int bh = blockIdx.x / p.nsplit;
     const int b = bh / p.H, h = bh - b * p.H;
 
-    int len = p.kv_len ? p.kv_len[b] : p.kv_len_all;
-    len = min(max(len, 0), p.kv_len_all);
+    // len: number of (virtual) tokens of this sequence
+    int len, rb = 0;
+    const int kc_tokens = kIndexed ? p.k_chunks * p.chunk : 0;
+    if constexpr (kIndexed) {
+        int full = p.kv_len ? p.kv_len[b] : p.full_len_all;
+        full = min(max(full, 0), p.full_len_all);
+        rb = p.recent_begin ? p.recent_begin[b] : p.recent_begin_all;
+        rb = min(max(rb, p.recent_begin_all), full);      // never below the promised lower bound
+        len = min(kc_tokens + (full - rb), p.kv_len_all);
+    } else {
+        len = p.kv_len ? p.kv_len[b] : p.kv_len_all;
+        len = min(max(len, 0), p.kv_len_all);
+    }
     const int64_t tb64 = (int64_t)split * p.tokens_per_split;
     const int t_begin = (int)(tb64 < (int64_t)len ? tb64 : (int64_t)len);
     const int t_end = (int)(tb64 + p.tokens_per_split < (int64_t)len ? tb64 + p.tokens_per_split : (int64_t)len);
@@ -86,15 +106,49 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     for (int e = 0; e < 8; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
-    auto load_k = [&](int t0, uint4(&k)[4]) {
-        const char *base = Kb + (int64_t)t0 * row_bytes;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) k[kk] = ld16(base + k_off + kk * 64);
+    // indexed mode: cache row of virtual token v, or -1 if it does not exist
+    auto virtual_row = [&](int v) -> int {
+        int row = -1;
+        if (v < kc_tokens) {
+            const int j = v / p.chunk;
+            const int m = p.idx[(int64_t)bh * p.k_chunks + j];
+            if (m >= 0 && (int64_t)(m + 1) * p.chunk <= (int64_t)p.full_len_all) row = m * p.chunk + (v - j * p.chunk);
+        } else if (v < len) {
+            row = rb + (v - kc_tokens);
+        }
+        return row;
     };
-    auto load_v = [&](int t0, uint4(&v)[4]) {
-        const char *base = Vb + (int64_t)t0 * row_bytes;
+
+    // loads of one tile; `rows` (indexed mode) is this lane's row for token t0+r, -1 = masked
+    auto load_k = [&](int t0, uint4(&k)[4], int &rows) {
+        if constexpr (kIndexed) {
+            rows = virtual_row(t0 + r);
+            const char *kp = Kb + (int64_t)max(rows, 0) * row_bytes + s * 16;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = ld16(base + v_off[i]);
+            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16(kp + kk * 64);
+        } else {
+            const char *base = Kb + (int64_t)t0 * row_bytes;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16(base + k_off + kk * 64);
+        }
+    };
+    // returns (indexed mode) the 4-bit validity mask of this lane's tokens 4s+i
+    auto load_v = [&](int t0, uint4(&v)[4], int rows) -> int {
+        int vm = 0xf;
+        if constexpr (kIndexed) {
+            vm = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int rv = __shfl(rows, 4 * s + i, kWave);   // row of token 4s+i (held by lane r'=4s+i)
+                vm |= (rv >= 0) << i;
+                v[i] = ld16(Vb + (int64_t)max(rv, 0) * row_bytes + r * 16);
+            }
+        } else {
+            const char *base = Vb + (int64_t)t0 * row_bytes;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = ld16(base + v_off[i]);
+        }
+        return vm;
     };
 
     // S^T tile: four bf16 MFMAs over the head dim, then the log2-domain scale
@@ -113,11 +167,11 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     };
 
     // online softmax of one tile and the P.V product
-    auto softmax_pv = [&](int t0, float(&z)[4], const uint4(&v)[4]) {
-        if (t0 + kTile > n_all) {  // wave-uniform: only tiles that touch the causal / ragged tail
+    auto softmax_pv = [&](int t0, float(&z)[4], const uint4(&v)[4], int vm) {
+        if (kIndexed || t0 + kTile > n_all) {  // wave-uniform: tiles touching the causal / ragged tail
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (t0 + 4 * s + i >= n_mine) z[i] = -INFINITY;
+                if (t0 + 4 * s + i >= n_mine || !((vm >> i) & 1)) z[i] = -INFINITY;
         }
         float mt = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
         mt = wave_max_xor(mt, 16);
@@ -150,47 +204,50 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         }
     };
 
-    // Whole 16-token tiles of this split, interleaved over the 4 waves. K of the next tile is
+    // 16-token tiles of this split, interleaved over the 4 waves. K of the next tile is
     // requested before the current QK^T, V of the next tile right after it (when the current
-    // K registers are dead), so one tile of loads is always in flight per wave.
-    const int n_full = (t_end - t_begin) / kTile;            // whole tiles in the split
+    // K registers are dead), so one tile of loads is always in flight per wave. Plain mode
+    // walks whole tiles here and leaves a ragged last tile to the clamped path below; indexed
+    // mode masks per token anyway, so the ragged tile is just one more tile.
+    const int n_full = kIndexed ? (t_end - t_begin + kTile - 1) / kTile : (t_end - t_begin) / kTile;
     const int n_mine_tiles = (n_full - wave + kWaves - 1) / kWaves;
     if (n_mine_tiles > 0) {
         constexpr int step = kWaves * kTile;
         uint4 ka[4], va[4], kb2[4], vb2[4];
+        int ra = 0, rb2 = 0, ma = 0xf, mb = 0xf;
         float z[4];
         int t0 = t_begin + wave * kTile;
         int left = n_mine_tiles;  // tiles not yet computed; buffer A always holds the next one
-        load_k(t0, ka);
-        load_v(t0, va);
+        load_k(t0, ka, ra);
+        ma = load_v(t0, va, ra);
         // steady state: no conditional loads, so the wait counters stay exact
         while (left > 2) {
-            load_k(t0 + step, kb2);
+            load_k(t0 + step, kb2, rb2);
             qk_tile(ka, z);
-            load_v(t0 + step, vb2);
-            softmax_pv(t0, z, va);
-            load_k(t0 + 2 * step, ka);
+            mb = load_v(t0 + step, vb2, rb2);
+            softmax_pv(t0, z, va, ma);
+            load_k(t0 + 2 * step, ka, ra);
             qk_tile(kb2, z);
-            load_v(t0 + 2 * step, va);
-            softmax_pv(t0 + step, z, vb2);
+            ma = load_v(t0 + 2 * step, va, ra);
+            softmax_pv(t0 + step, z, vb2, mb);
             t0 += 2 * step;
             left -= 2;
         }
         if (left == 2) {
-            load_k(t0 + step, kb2);
+            load_k(t0 + step, kb2, rb2);
             qk_tile(ka, z);
-            load_v(t0 + step, vb2);
-            softmax_pv(t0, z, va);
+            mb = load_v(t0 + step, vb2, rb2);
+            softmax_pv(t0, z, va, ma);
             qk_tile(kb2, z);
-            softmax_pv(t0 + step, z, vb2);
+            softmax_pv(t0 + step, z, vb2, mb);
         } else {
             qk_tile(ka, z);
-            softmax_pv(t0, z, va);
+            softmax_pv(t0, z, va, ma);
         }
     }
-    // ragged tail (len not a multiple of 16): one partial tile, rows clamped to the last valid
-    // token and masked; handled by the wave whose turn it would be
-    if (t_begin + n_full * kTile < t_end && (n_full % kWaves) == wave) {
+    // plain mode, ragged tail (len not a multiple of 16): one partial tile, rows clamped to the
+    // last valid token and masked; handled by the wave whose turn it would be
+    if (!kIndexed && t_begin + n_full * kTile < t_end && (n_full % kWaves) == wave) {
         const int t0 = t_begin + n_full * kTile;
         uint4 kt[4], vt[4];
         float z[4];
@@ -201,7 +258,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         for (int i = 0; i < 4; ++i)
             vt[i] = ld16(Vb + (int64_t)min(t0 + 4 * s + i, last_row) * row_bytes + r * 16);
         qk_tile(kt, z);
-        softmax_pv(t0, z, vt);
+        softmax_pv(t0, z, vt, 0xf);
     }
 
     // total of the per-lane partial sums of each query (lanes (r, 0..3))
@@ -387,9 +444,23 @@ size_t attn_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, in
     return attn_ws_bytes(BH, plan_splits(BH, kv_len_all, retrieval));
 }
 
+
+static int64_t virtual_len_all(const IndexedArgs &ix, int64_t kv_len_all) {
+    return (int64_t)ix.k_chunks * ix.chunk + (kv_len_all - ix.recent_begin_all);
+}
+
+size_t attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chunks, int32_t chunk,
+                                    int64_t recent_len_all, int32_t G) {
+    if (batch <= 0 || heads <= 0 || k_chunks < 0 || chunk <= 0 || recent_len_all < 0 || G <= 0) return 0;
+    const int64_t lv = (int64_t)k_chunks * chunk + recent_len_all;
+    if (lv <= 0) return 0;
+    const int64_t BH = (int64_t)batch * heads;
+    return attn_ws_bytes(BH, plan_splits(BH, lv, true));
+}
+
 int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
                 int64_t kv_len_all, int32_t G, float scale, int32_t causal, float *O, float *LSE, void *ws,
-                size_t ws_bytes, void *stream, bool retrieval) {
+                size_t ws_bytes, void *stream, bool retrieval, const IndexedArgs *ix) {
     if (!Q || !K || !V || !O) return TF_ERR_INVALID_ARG;
     int rc = check_desc(kd);
     if (rc != TF_OK) return rc;
@@ -397,11 +468,21 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     if (G > TF_MAX_QUERIES) return TF_ERR_UNSUPPORTED;
     if (kv_len_all < 1 || kv_len_all > kd->capacity) return TF_ERR_INVALID_ARG;
     if (kd->capacity > (int64_t)1 << 30 || kd->stride_t > (1 << 24)) return TF_ERR_UNSUPPORTED;
-    if (causal && kv_len_all < G) return TF_ERR_INVALID_ARG;
+    int64_t plan_len = kv_len_all;  // length the splits are planned on
+    if (ix) {
+        if (ix->k_chunks < 0 || ix->chunk < 1 || (ix->k_chunks > 0 && !ix->idx)) return TF_ERR_INVALID_ARG;
+        if (ix->chunk > 64) return TF_ERR_UNSUPPORTED;
+        if (ix->recent_begin_all < 0 || ix->recent_begin_all > kv_len_all) return TF_ERR_INVALID_ARG;
+        if (causal && kv_len_all - ix->recent_begin_all < G) return TF_ERR_INVALID_ARG;  // queries are recent rows
+        plan_len = virtual_len_all(*ix, kv_len_all);
+        if (plan_len < 1) return TF_ERR_INVALID_ARG;
+        if (plan_len > (int64_t)1 << 30) return TF_ERR_UNSUPPORTED;
+    }
+    if (causal && plan_len < G) return TF_ERR_INVALID_ARG;
     if (!(scale == scale) || scale - scale != 0.f) return TF_ERR_INVALID_ARG;  // NaN or infinite
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return TF_ERR_INVALID_ARG;
     const int64_t BH = (int64_t)kd->batch * kd->heads;
-    const SplitPlan sp = plan_splits(BH, kv_len_all, retrieval);
+    const SplitPlan sp = plan_splits(BH, plan_len, retrieval);
     if (BH * sp.nsplit >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
     if (!ws || !aligned(ws, 256) || ws_bytes < attn_ws_bytes(BH, sp)) return TF_ERR_WORKSPACE;
 
@@ -413,7 +494,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.sh = kd->stride_h;
     p.st = kd->stride_t;
     p.kv_len = kv_len;
-    p.kv_len_all = (int32_t)kv_len_all;
+    p.kv_len_all = (int32_t)plan_len;
     p.H = kd->heads;
     p.G = G;
     p.causal = causal ? 1 : 0;
@@ -422,9 +503,19 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.scale_log2 = scale * kLog2e;
     p.part_o = static_cast<float *>(ws);
     p.part_ml = p.part_o + (size_t)BH * sp.nsplit * kGPad * kHeadDim;
+    p.idx = ix ? ix->idx : nullptr;
+    p.k_chunks = ix ? ix->k_chunks : 0;
+    p.chunk = ix ? ix->chunk : 1;
+    p.recent_begin = ix ? ix->recent_begin : nullptr;
+    p.recent_begin_all = ix ? (int32_t)ix->recent_begin_all : 0;
+    p.full_len_all = (int32_t)kv_len_all;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(attn_split_kernel, dim3((unsigned)(BH * sp.nsplit)), dim3(256), 0, st, p);
+    const dim3 grid((unsigned)(BH * sp.nsplit));
+    if (ix)
+        hipLaunchKernelGGL(attn_split_kernel<true>, grid, dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL(attn_split_kernel<false>, grid, dim3(256), 0, st, p);
     hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(BH * G)), dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
                        sp.nsplit, G, O, LSE);
     return hip_status(hipGetLastError());

@@ -41,4 +41,13 @@ inline int check_desc(const tf_kv_desc *d) {
     return TF_OK;
 }
 
+// indexed attention: the virtual sequence is chunks idx[0..k_chunks) of the cache followed by
+// the cache rows [recent_begin, len)
+struct IndexedArgs {
+    const int32_t *idx;
+    int32_t k_chunks, chunk;
+    const int32_t *recent_begin;
+    int64_t recent_begin_all;
+};
+
 }  // namespace tf
