@@ -99,6 +99,7 @@ class Step:
             a["out"] = torch.empty((B, G), dtype=torch.int32, device=device)
         nbytes = max(tf.tf_decode_attn_full_workspace_bytes(B, H, N, w.G),
                      tf.tf_decode_attn_retrieval_workspace_bytes(B, H, w.R, w.G_d),
+                     tf.tf_decode_attn_indexed_workspace_bytes(B, H, w.k, w.c, w.G_d, w.G_d),
                      tf.tf_chunk_topk_gather_workspace_bytes(LB, H, w.M, w.k),
                      tf.tf_spec_accept_workspace_bytes(B, w.G, w.V))
         self.ws = tf.workspace(nbytes, device)
@@ -128,6 +129,15 @@ class Step:
         self.tf.tf_decode_attn_full(self.layer(self.Q, l), self.layer(self.K, l), self.layer(self.V, l),
                                     self.layer(self.O, l), self.layer(self.LSE, l), scale=1.0, causal=True,
                                     ws=self.ws)
+
+    def draft_attn_indexed(self, l):
+        """Gather-free variant of the draft pass: through the chunk indices into the full cache;
+        the G_d query tokens' own rows are the last rows of the full cache."""
+        w = self.w
+        self.tf.tf_decode_attn_indexed(self.layer(self.Q_d, l), self.layer(self.K, l), self.layer(self.V, l),
+                                       self.layer(self.idx, l), w.c, self.layer(self.O_d, l),
+                                       self.layer(self.LSE_d, l), kv_len_all=w.N, recent_begin_all=w.N - w.G_d,
+                                       scale=1.0, causal=True, ws=self.ws)
 
     def accept(self, a):
         self.tf.tf_spec_accept(a["target_logits"], a["draft_logits"], a["draft_tokens"], self.T,
@@ -258,6 +268,13 @@ def main():
     verify_avg_s = float(np.mean(verify_ms)) * 1e-3
     achieved = w.kv_bytes_per_layer() / verify_avg_s / 1e9
     breakdown = step.breakdown()
+    # rows beyond the five calls, timed outside the step: gather-free draft pass over all layers
+    for l in range(L):
+        step.draft_attn_indexed(l)
+    torch.cuda.synchronize()
+    ev = [_timed(lambda: [step.draft_attn_indexed(l) for l in range(L)]) for _ in range(3)]
+    torch.cuda.synchronize()
+    indexed_us = float(np.mean([a.elapsed_time(b) for a, b in ev])) * 1e3
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
@@ -286,6 +303,7 @@ def main():
         "breakdown_us_per_step": breakdown,
         "one_time": {"chunk_summarize_all_layers_us": round(summarize_all_us, 1),
                      "chunk_summarize_gbps": round(summ_bytes / summarize_all_us / 1e3, 1)},
+        "extra": {"decode_attn_indexed_us_per_step": round(indexed_us, 1)},
         "roofline": {"bound": "hbm", "kernel": "attn_split_kernel (tf_decode_attn_full)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
