@@ -28,6 +28,8 @@ __device__ __forceinline__ const float *logits_row(const AcceptParams &p, int b,
                     : p.dl + ((int64_t)b * (p.G - 1) + (rr - p.G)) * p.V;
 }
 
+constexpr int kAccReg = 32;  // logits per thread kept in registers (covers V <= 32768)
+
 __global__ __launch_bounds__(kAccThreads) void accept_rowstats_kernel(const AcceptParams p) {
     __shared__ double red_d[kAccThreads / 64];
     __shared__ float red_f[kAccThreads / 64];
@@ -36,15 +38,36 @@ __global__ __launch_bounds__(kAccThreads) void accept_rowstats_kernel(const Acce
     const int rows = 2 * p.G - 1;
     const int b = blockIdx.x / rows, rr = blockIdx.x - b * rows;
     const float *x = logits_row(p, b, rr);
+    const bool in_regs = p.V <= kAccReg * kAccThreads;  // uniform
 
+    // one round trip to memory: every thread's strided share of the row, all loads in flight
+    float xs[kAccReg];
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < kAccReg; ++j) {
+            const int v = tid + j * kAccThreads;
+            xs[j] = v < p.V ? x[v] : -INFINITY;
+        }
+    }
     // maximum logit and its first index
     float mx = -INFINITY;
     int mi = 0x7fffffff;
-    for (int v = tid; v < p.V; v += kAccThreads) {
-        const float f = x[v];
-        if (f > mx || (f == mx && v < mi)) {
-            mx = f;
-            mi = v;
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < kAccReg; ++j) {
+            const int v = tid + j * kAccThreads;
+            if (v < p.V && (xs[j] > mx || (xs[j] == mx && v < mi))) {
+                mx = xs[j];
+                mi = v;
+            }
+        }
+    } else {
+        for (int v = tid; v < p.V; v += kAccThreads) {
+            const float f = x[v];
+            if (f > mx || (f == mx && v < mi)) {
+                mx = f;
+                mi = v;
+            }
         }
     }
 #pragma unroll
@@ -81,7 +104,13 @@ __global__ __launch_bounds__(kAccThreads) void accept_rowstats_kernel(const Acce
     }
     const double zmax = (double)mx / p.T;
     double sum = 0.0;
-    for (int v = tid; v < p.V; v += kAccThreads) sum += exp((double)x[v] / p.T - zmax);
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < kAccReg; ++j)
+            if (tid + j * kAccThreads < p.V) sum += exp((double)xs[j] / p.T - zmax);
+    } else {
+        for (int v = tid; v < p.V; v += kAccThreads) sum += exp((double)x[v] / p.T - zmax);
+    }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
     if (lane == 0) red_d[wave] = sum;
@@ -104,27 +133,32 @@ __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const Accept
     const int32_t *x = p.toks + (int64_t)b * gamma;
     int32_t *out = p.out + (int64_t)b * p.G;
 
-    if (tid == 0) {
-        int n = 0;
-        for (; n < gamma; ++n) {
-            const int tok = x[n];
-            bool ok = tok >= 0 && tok < p.V;
+    // accept walk: lane i of the first wave evaluates drafted position i, a ballot finds the
+    // first rejection
+    if (tid < 64) {
+        bool ok = true;
+        if (tid < gamma) {
+            const int tok = x[tid];
+            ok = tok >= 0 && tok < p.V;
             if (ok) {
                 if (p.T == 0.0) {
-                    ok = tok == (int)st[n * 2];
+                    ok = tok == (int)st[tid * 2];
                 } else {
-                    const double pt = exp((double)logits_row(p, b, n)[tok] / p.T - st[n * 2]) / st[n * 2 + 1];
-                    const double qt = exp((double)logits_row(p, b, p.G + n)[tok] / p.T - st[(p.G + n) * 2]) /
-                                      st[(p.G + n) * 2 + 1];
-                    ok = (double)p.ua[(int64_t)b * gamma + n] * qt < pt;
+                    const double pt = exp((double)logits_row(p, b, tid)[tok] / p.T - st[tid * 2]) / st[tid * 2 + 1];
+                    const double qt = exp((double)logits_row(p, b, p.G + tid)[tok] / p.T - st[(p.G + tid) * 2]) /
+                                      st[(p.G + tid) * 2 + 1];
+                    ok = (double)p.ua[(int64_t)b * gamma + tid] * qt < pt;
                 }
             }
-            if (!ok) break;
         }
-        s_n = n;
-        s_rej = n < gamma;
-        s_tok = 0x7fffffff;
-        s_last = -1;
+        const unsigned long long rej = __builtin_amdgcn_ballot_w64(!ok);
+        if (tid == 0) {
+            const int n = rej ? __builtin_ctzll(rej) : gamma;
+            s_n = n;
+            s_rej = n < gamma;
+            s_tok = 0x7fffffff;
+            s_last = -1;
+        }
     }
     __syncthreads();
     const int n = s_n, rejected = s_rej;
@@ -138,7 +172,8 @@ __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const Accept
         return;
     }
 
-    // distribution to draw from: residual of row n if rejected, else target row gamma (= n)
+    // distribution to draw from: residual of row n if rejected, else target row gamma (= n).
+    // Thread t owns the contiguous index range [t*per, (t+1)*per) so the scan is in index order.
     const float *tl = logits_row(p, b, n);
     const float *dl = rejected ? logits_row(p, b, p.G + n) : tl;
     const double tz = st[n * 2], ts = st[n * 2 + 1];
@@ -147,15 +182,36 @@ __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const Accept
     const int v_lo = min(tid * per, p.V), v_hi = min(p.V, v_lo + per);
 
     bool use_p = !rejected;  // second round only if the residual is identically zero
+    auto mass_of = [&](float t, float dq) -> double {
+        const double pv = exp((double)t / p.T - tz) / ts;
+        if (use_p) return pv;
+        const double qv = exp((double)dq / p.T - dz) / ds;
+        return pv - qv > 0.0 ? pv - qv : 0.0;
+    };
+    // logits are fetched 8 at a time so that the loads of a group are in flight together
+    auto load8 = [&](int v0, float(&t8)[8], float(&d8)[8]) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int v = v0 + j;
+            t8[j] = v < v_hi ? tl[v] : -INFINITY;
+            d8[j] = (rejected && v < v_hi) ? dl[v] : -INFINITY;
+        }
+    };
     for (int round = 0; round < 2; ++round) {
-        auto mass = [&](int v) -> double {
-            const double pv = exp((double)tl[v] / p.T - tz) / ts;
-            if (use_p) return pv;
-            const double qv = exp((double)dl[v] / p.T - dz) / ds;
-            return pv - qv > 0.0 ? pv - qv : 0.0;
-        };
         double local = 0.0;
-        for (int v = v_lo; v < v_hi; ++v) local += mass(v);
+        int lastpos = -1;  // last index of this range with positive mass
+#pragma unroll 1
+        for (int v0 = v_lo; v0 < v_hi; v0 += 8) {
+            float t8[8], d8[8];
+            load8(v0, t8, d8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (v0 + j < v_hi) {
+                    const double mv = mass_of(t8[j], d8[j]);
+                    local += mv;
+                    if (mv > 0.0) lastpos = v0 + j;
+                }
+        }
         double incl = local;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -176,19 +232,25 @@ __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const Accept
         }
         const double target = (double)p.us[b] * Z;
         double cum = before + incl - local;
-        int found = 0x7fffffff, lastpos = -1;
-        for (int v = v_lo; v < v_hi; ++v) {
-            const double mv = mass(v);
-            cum += mv;
-            if (mv > 0.0) lastpos = v;
-            if (cum > target) {
-                found = v;
-                break;
+        // only ranges whose end lies above the target are walked: the one holding the answer
+        // and those behind it (which stop at their first positive entry)
+        int found = 0x7fffffff;
+        if (cum + local > target) {
+#pragma unroll 1
+            for (int v0 = v_lo; v0 < v_hi && found == 0x7fffffff; v0 += 8) {
+                float t8[8], d8[8];
+                load8(v0, t8, d8);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (found == 0x7fffffff && v0 + j < v_hi) {
+                        const double mv = mass_of(t8[j], d8[j]);
+                        cum += mv;
+                        if (cum > target) found = v0 + j;
+                    }
             }
         }
         if (found != 0x7fffffff) atomicMin(&s_tok, found);
-        // only needed when rounding leaves no cell above the target: every thread then
-        // walked its whole range, so lastpos is the last positive entry of that range
+        // used only when rounding leaves no cell above the target: the last positive entry
         if (lastpos >= 0) atomicMax(&s_last, lastpos);
         break;
     }

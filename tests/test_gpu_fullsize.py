@@ -1,7 +1,7 @@
 """GPU parity at the full per-layer sizes of the specified workloads, in the launch configuration
 bench.py times (default split planning, one layer = all batch x head units). Inputs are drawn by
-the seeded device generator; a sample of (batch, head) units is copied to the host and the oracle
-computes their outputs one by one. Properties that hold at any size are checked on every unit.
+the seeded device generator and copied to the host one layer at a time; the oracle then computes
+every (batch, head) unit of the layer. Properties that hold at any size are checked as well.
 """
 import numpy as np
 import pytest
@@ -21,21 +21,14 @@ def say(msg):
     print(msg, flush=True)
 
 
-def _unit(t, b, h):
-    """One (b,h) unit of a device tensor as a host uint16 / numpy array with unit batch and head dims."""
-    x = t[b:b + 1, h:h + 1].contiguous()
-    return synth.as_u16(x) if x.dtype == torch.bfloat16 else x.cpu().numpy()
-
-
-@pytest.mark.parametrize("name,units", [
-    ("step128k", [(0, 0), (0, 13), (0, 31)]),
-    ("batch4x64k", [(0, 5), (2, 17), (3, 31)]),
-    ("extreme1m", [(0, 7), (0, 30)]),
+@pytest.mark.parametrize("name,layer", [
+    ("step128k", 0), ("step128k", 31),
+    ("batch4x64k", 1),
+    ("extreme1m", 1),
 ])
-def test_one_layer_at_full_size(name, units):
+def test_one_layer_at_full_size(name, layer):
     w = synth.WORKLOADS[name]
-    layer = 1
-    say(f"case fullsize {name} layer={layer} seed={synth.seed_for(w, layer)} units={units}")
+    say(f"case fullsize {name} layer={layer} seed={synth.seed_for(w, layer)}")
     x = synth.make_workload_layer(w, layer, DEV)
     K, V, Q, q_r = x["K"], x["V"], x["Q"], x["q_r"]
     B, H, N, d = K.shape
@@ -63,7 +56,7 @@ def test_one_layer_at_full_size(name, units):
     assert idx_h.min() >= 0 and idx_h.max() < w.M
     srt = np.sort(idx_h, axis=-1)
     assert np.all(srt[..., 1:] > srt[..., :-1])                       # distinct
-    sc_h = score.cpu().numpy()
+    sc_h = score.cpu().numpy().astype(np.float64)
     assert np.all(sc_h[..., 1:] <= sc_h[..., :-1])                    # descending importance
     planted = x["planted"].cpu().numpy()
     for b in range(B):
@@ -79,38 +72,45 @@ def test_one_layer_at_full_size(name, units):
     assert torch.isfinite(O).all() and torch.isfinite(L).all() and torch.isfinite(O_d).all()
     del gi, rows
 
-    # sampled units against the oracle ----------------------------------------------------
-    for (b, h) in units:
-        Ku, Vu, Qu = _unit(K, b, h), _unit(V, b, h), _unit(Q, b, h)
-        km = oracle.chunk_mean(Ku, w.c)
-        got_km = Kmean[b, h].cpu().numpy().astype(np.float64)
-        assert np.max(np.abs(got_km - km[0, 0])) < 2e-7 * max(1.0, np.abs(km).max())
-        o_scores, o_idx = oracle.retrieve(_unit(q_r, b, h)[:, :, :], km, w.k)
-        s = o_scores[0, 0]
-        got = idx_h[b, h]
-        tau = s[o_idx[0, 0, -1]]
-        assert set(np.where(s > tau + TIE_BAND)[0].tolist()) <= set(got.tolist())
-        assert not (set(got.tolist()) & set(np.where(s < tau - TIE_BAND)[0].tolist()))
-        along = s[got]
-        assert np.all(along[1:] <= along[:-1] + TIE_BAND)
-        assert np.max(np.abs(sc_h[b, h] - along)) < 2e-5 * max(1.0, np.abs(along).max())
-        same_set = set(got.tolist()) == set(o_idx[0, 0].tolist())
-        # verification attention over the full cache
-        Oo, Lo, _ = oracle.attention(Qu, Ku, Vu, scale=1.0, causal=True)
-        e = float(np.max(np.abs(O[b, h].cpu().numpy() - Oo[0, 0])))
-        el = float(np.max(np.abs(L[b, h].cpu().numpy() - Lo[0, 0])))
-        # draft attention over the retrieval cache (comparable when the selected set is unique)
-        ed = float("nan")
-        if same_set:
-            oKr, oVr = oracle.gather(Ku, Vu, o_idx, w.c)
-            Od, Ld, _ = oracle.attention(np.ascontiguousarray(Qu[:, :, -w.G_d:, :]), oKr, oVr, scale=1.0,
-                                         causal=False)
-            ed = float(np.max(np.abs(O_d[b, h].cpu().numpy() - Od[0, 0])))
-            assert ed <= ATTN_TOL
-            assert np.max(np.abs(L_d[b, h].cpu().numpy() - Ld[0, 0])) <= LSE_TOL
-        say(f"[{name}] unit {(b, h)}: verify max|dO|={e:.2e} max|dLSE|={el:.2e}; "
-            f"same chunk set={same_set}; draft max|dO|={ed:.2e}")
-        assert e <= ATTN_TOL and el <= LSE_TOL
+    # every unit against the oracle -------------------------------------------------------
+    Ku, Vu, Qu = synth.as_u16(K), synth.as_u16(V), synth.as_u16(Q)
+    del K, V, x
+    torch.cuda.empty_cache()
+    km = oracle.chunk_mean(Ku, w.c)
+    got_km = Kmean.cpu().numpy()
+    e_km = float(np.max(np.abs(got_km - km)))
+    assert e_km < 2e-7 * max(1.0, float(np.abs(km).max()))
+    del got_km
+    o_scores, o_idx = oracle.retrieve(synth.as_u16(q_r), km, w.k)
+    del km
+    exact = unique = 0
+    for b in range(B):
+        for h in range(H):
+            s, got = o_scores[b, h], idx_h[b, h]
+            tau = s[o_idx[b, h, -1]]
+            assert set(np.where(s > tau + TIE_BAND)[0].tolist()) <= set(got.tolist())
+            assert not (set(got.tolist()) & set(np.where(s < tau - TIE_BAND)[0].tolist()))
+            along = s[got]
+            assert np.all(along[1:] <= along[:-1] + TIE_BAND)
+            assert np.max(np.abs(sc_h[b, h] - along)) < 2e-5 * max(1.0, np.abs(along).max())
+            exact += int(np.array_equal(got, o_idx[b, h]))
+            unique += int(set(got.tolist()) == set(o_idx[b, h].tolist()))
+    say(f"[{name}] chunk means max err {e_km:.1e}; top-k: {exact}/{B * H} units identical in order, "
+        f"{unique}/{B * H} identical as sets")
+    # verification attention over the full cache, every unit
+    Oo, Lo, _ = oracle.attention(Qu, Ku, Vu, scale=1.0, causal=True)
+    e = float(np.max(np.abs(O.cpu().numpy() - Oo)))
+    el = float(np.max(np.abs(L.cpu().numpy() - Lo)))
+    say(f"[{name}] verify attention, all {B * H} units: max|dO|={e:.2e} max|dLSE|={el:.2e}")
+    assert e <= ATTN_TOL and el <= LSE_TOL
+    # draft attention over the retrieval cache: comparable on units whose selected set is unique
+    oKr, oVr = oracle.gather(Ku, Vu, o_idx, w.c)
+    Od, Ld, _ = oracle.attention(np.ascontiguousarray(Qu[:, :, -w.G_d:, :]), oKr, oVr, scale=1.0, causal=False)
+    same = np.array([[set(idx_h[b, h].tolist()) == set(o_idx[b, h].tolist()) for h in range(H)] for b in range(B)])
+    ed = float(np.max(np.abs(O_d.cpu().numpy() - Od)[same]))
+    eld = float(np.max(np.abs(L_d.cpu().numpy() - Ld)[same]))
+    say(f"[{name}] draft attention on {int(same.sum())} units: max|dO|={ed:.2e} max|dLSE|={eld:.2e}")
+    assert same.sum() >= 0.9 * B * H and ed <= ATTN_TOL and eld <= LSE_TOL
 
 
 @pytest.mark.parametrize("gamma", [2, 4, 6])
