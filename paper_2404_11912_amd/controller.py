@@ -1,0 +1,119 @@
+"""Host controller of the hierarchical speculation loop (Algorithm 1) and the retrieval-cache
+rebuild policy (Sec. 4.3). Host logic only: every accept / resample decision and every draw
+runs in `tf_spec_accept` on the GPU; the three "models" are callbacks returning logits, so the
+controller works with real forward passes as well as with synthetic logits tables.
+
+Notation follows Algorithm 1: M_q is the small draft model (logits q_i), M_p with the retrieval
+cache gives p-hat_i, M_p with the full cache gives p_i; gamma1 / gamma2 are the two speculation
+lengths; N counts generated tokens.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+from . import binding as tf
+
+
+@dataclass
+class RebuildPolicy:
+    """When to rebuild the retrieval cache (Sec. 4.3): at a fixed stride of verification steps,
+    or when the rolling average acceptance rate of the verification level drops below a
+    threshold. stride = 0 / threshold = 0 switch the respective trigger off."""
+    stride: int = 0
+    threshold: float = 0.0
+    window: int = 16
+    _steps: int = 0
+    _hist: list = field(default_factory=list)
+
+    def update(self, accepted: int, drafted: int) -> bool:
+        self._steps += 1
+        if drafted > 0:
+            self._hist.append(accepted / drafted)
+            self._hist = self._hist[-self.window:]
+        by_stride = self.stride > 0 and self._steps % self.stride == 0
+        by_rate = (self.threshold > 0.0 and len(self._hist) == self.window
+                   and sum(self._hist) / len(self._hist) < self.threshold)
+        if by_stride or by_rate:
+            self._hist = []
+            return True
+        return False
+
+
+class TriForceController:
+    """Algorithm 1 for one sequence.
+
+    draft_fn(pos, n)     -> fp32 logits [n, V] of M_q for generated positions pos .. pos+n-1
+    retrieval_fn(pos, n) -> fp32 logits [n, V] of M_p over the retrieval cache (p-hat)
+    target_fn(pos, n)    -> fp32 logits [n, V] of M_p over the full cache (p)
+    uniform(n)           -> n fp32 uniforms in [0,1) as a numpy array (the caller's seeded source;
+                            consumed in a fixed order so a reference can replay them)
+    on_update(tokens, rebuild) is called after every verification with the newly fixed tokens.
+    """
+
+    def __init__(self, draft_fn, retrieval_fn, target_fn, uniform, vocab: int, gamma1: int = 2, gamma2: int = 6,
+                 temperature: float = 0.6, policy: RebuildPolicy | None = None, on_update=None, device="cuda"):
+        if gamma1 < 1 or gamma2 < 1 or gamma1 + gamma2 + 1 > tf.TF_MAX_SPEC:
+            raise ValueError("need 1 <= gamma1, gamma2 and gamma1 + gamma2 + 1 <= TF_MAX_SPEC")
+        self.draft_fn, self.retrieval_fn, self.target_fn, self.uniform = draft_fn, retrieval_fn, target_fn, uniform
+        self.V, self.g1, self.g2, self.T = vocab, gamma1, gamma2, float(temperature)
+        self.policy, self.on_update, self.dev = policy or RebuildPolicy(), on_update, torch.device(device)
+        self.ws = tf.workspace(tf.tf_spec_accept_workspace_bytes(gamma1, tf.TF_MAX_SPEC, vocab), self.dev)
+        self.stats = {"outer_steps": 0, "inner_steps": 0, "drafted_l1": 0, "accepted_l1": 0, "drafted_l2": 0,
+                      "accepted_l2": 0, "rebuilds": 0}
+
+    def _u(self, n):
+        return torch.from_numpy(np.ascontiguousarray(self.uniform(n), dtype=np.float32)).to(self.dev)
+
+    def _accept(self, target_logits, draft_logits, draft_tokens, u_accept, u_sample):
+        """One tf_spec_accept call for a single sequence; returns (n_accepted, emitted tokens list)."""
+        G = target_logits.shape[0]
+        n = torch.empty((1,), dtype=torch.int32, device=self.dev)
+        out = torch.empty((1, G), dtype=torch.int32, device=self.dev)
+        tf.tf_spec_accept(target_logits[None].contiguous(),
+                          None if G == 1 else draft_logits[None].contiguous(),
+                          None if G == 1 else draft_tokens[None].contiguous(), self.T,
+                          None if G == 1 else u_accept[None].contiguous(), u_sample, n, out, ws=self.ws)
+        n_acc = int(n.item())
+        return n_acc, out[0, :n_acc + 1].tolist()
+
+    def _sample_rows(self, logits, u):
+        """Draw one token from every row of `logits` (rows ride in the batch dimension, G = 1)."""
+        rows = logits.shape[0]
+        n = torch.empty((rows,), dtype=torch.int32, device=self.dev)
+        out = torch.empty((rows, 1), dtype=torch.int32, device=self.dev)
+        tf.tf_spec_accept(logits[:, None, :].contiguous(), None, None, self.T, None, u, n, out, ws=self.ws)
+        return out[:, 0].contiguous()
+
+    def generate(self, n_tokens: int):
+        """Run Algorithm 1 until at least n_tokens are generated; returns the token list."""
+        tokens, N = [], 0
+        while N < n_tokens:
+            n, x_hat = 0, []
+            while n < self.g2:                                   # first level: M_q drafts for M_p(C_r)
+                base = N + n
+                q = self.draft_fn(base, self.g1)
+                x_tilde = self._sample_rows(q, self._u(self.g1))
+                p_hat = self.retrieval_fn(base, self.g1 + 1)
+                n1, emitted = self._accept(p_hat, q, x_tilde, self._u(self.g1), self._u(1))
+                x_hat += emitted
+                n += n1 + 1
+                self.stats["inner_steps"] += 1
+                self.stats["drafted_l1"] += self.g1
+                self.stats["accepted_l1"] += n1
+            p = self.target_fn(N, n + 1)                         # second level: M_p(C_p) verifies x_hat
+            p_hat_all = self.retrieval_fn(N, n)
+            xs = torch.tensor(x_hat, dtype=torch.int32, device=self.dev)
+            n2, emitted = self._accept(p, p_hat_all, xs, self._u(n), self._u(1))
+            tokens += emitted
+            N += n2 + 1
+            self.stats["outer_steps"] += 1
+            self.stats["drafted_l2"] += n
+            self.stats["accepted_l2"] += n2
+            rebuild = self.policy.update(n2, n)
+            self.stats["rebuilds"] += int(rebuild)
+            if self.on_update is not None:
+                self.on_update(emitted, rebuild)
+        return tokens

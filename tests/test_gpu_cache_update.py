@@ -164,3 +164,22 @@ def test_retrieval_cache_maintenance_scenario():
         length += n_acc
         torch.cuda.synchronize()
         assert np.array_equal(synth.as_u16(Kr), oKr) and np.array_equal(synth.as_u16(Vr), oVr)
+
+
+def test_sinks_plus_recent_window_is_a_streaming_cache():
+    """The StreamingLLM cache shape (Sec. 2.2: attention sinks + recent tokens) is the indexed
+    call with the sink chunk(s) as indices and the window as the recent range."""
+    say("case streaming_cache seed=159")
+    B, H, N, G, c = 2, 4, 5000, 4, 4
+    x = synth.make_layer(B, H, N, G, c, 0, seed=159)
+    kv_len, window = [5000, 3777], 1020
+    rb = [n - window for n in kv_len]
+    idx = torch.zeros((B, H, 1), dtype=torch.int32, device=DEV)        # chunk 0 = the 4 sink tokens
+    O, L = _run_indexed(x["Q"].to(DEV), x["K"].to(DEV), x["V"].to(DEV), idx, c, kv_len=kv_len, recent_begin=rb,
+                        kv_len_all=N, recent_begin_all=min(rb))
+    Ku, Vu, Qu = synth.as_u16(x["K"]), synth.as_u16(x["V"]), synth.as_u16(x["Q"])
+    for b in range(B):
+        Kc = np.concatenate([Ku[b:b + 1, :, :c], Ku[b:b + 1, :, rb[b]:kv_len[b]]], axis=2)
+        Vc = np.concatenate([Vu[b:b + 1, :, :c], Vu[b:b + 1, :, rb[b]:kv_len[b]]], axis=2)
+        Oo, Lo, _ = oracle.attention(Qu[b:b + 1], Kc, Vc, causal=True)
+        assert np.max(np.abs(O[b] - Oo[0])) <= ATTN_TOL and np.max(np.abs(L[b] - Lo[0])) <= LSE_TOL
