@@ -125,11 +125,11 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
             rows = virtual_row(t0 + r);
             const char *kp = Kb + (int64_t)max(rows, 0) * row_bytes + s * 16;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16(kp + kk * 64);
+            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16_stream(kp + kk * 64);
         } else {
             const char *base = Kb + (int64_t)t0 * row_bytes;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16(base + k_off + kk * 64);
+            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16_stream(base + k_off + kk * 64);
         }
     };
     // returns (indexed mode) the 4-bit validity mask of this lane's tokens 4s+i
@@ -141,12 +141,12 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
             for (int i = 0; i < 4; ++i) {
                 const int rv = __shfl(rows, 4 * s + i, kWave);   // row of token 4s+i (held by lane r'=4s+i)
                 vm |= (rv >= 0) << i;
-                v[i] = ld16(Vb + (int64_t)max(rv, 0) * row_bytes + r * 16);
+                v[i] = ld16_stream(Vb + (int64_t)max(rv, 0) * row_bytes + r * 16);
             }
         } else {
             const char *base = Vb + (int64_t)t0 * row_bytes;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = ld16(base + v_off[i]);
+            for (int i = 0; i < 4; ++i) v[i] = ld16_stream(base + v_off[i]);
         }
         return vm;
     };
@@ -253,10 +253,10 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         float z[4];
         const char *kp = Kb + (int64_t)min(t0 + r, last_row) * row_bytes + s * 16;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) kt[kk] = ld16(kp + kk * 64);
+        for (int kk = 0; kk < 4; ++kk) kt[kk] = ld16_stream(kp + kk * 64);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            vt[i] = ld16(Vb + (int64_t)min(t0 + 4 * s + i, last_row) * row_bytes + r * 16);
+            vt[i] = ld16_stream(Vb + (int64_t)min(t0 + 4 * s + i, last_row) * row_bytes + r * 16);
         qk_tile(kt, z);
         softmax_pv(t0, z, vt, 0xf);
     }

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void chunk_summarize_kernel(const SumParams p)
             uint4 v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (i0 + u < c) v[u] = ld16(src + (int64_t)(i0 + u) * p.st);
+                if (i0 + u < c) v[u] = ld16_stream(src + (int64_t)(i0 + u) * p.st);
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (i0 + u < c) {

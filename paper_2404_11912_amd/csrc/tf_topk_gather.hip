@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) void chunk_score_kernel(const ScoreParams p) {
         const float *row = base + (int64_t)m_ld * kHeadDim;
         float4 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4 *>(row + 16 * j);
+        for (int j = 0; j < 8; ++j) v[j] = ldf4_stream(row + 16 * j);
         float acc = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -258,8 +258,8 @@ __global__ __launch_bounds__(256) void chunk_gather_kernel(const GatherParams p)
     const int64_t dst = (int64_t)b * p.rb + (int64_t)h * p.rh + (int64_t)j * p.chunk * p.rt + (lane & 15) * 8;
 #pragma unroll 2
     for (int i = lane >> 4; i < p.chunk; i += 4) {
-        const uint4 kv = ld16(p.K + src + (int64_t)i * p.st);
-        const uint4 vv = ld16(p.V + src + (int64_t)i * p.st);
+        const uint4 kv = ld16_stream(p.K + src + (int64_t)i * p.st);
+        const uint4 vv = ld16_stream(p.V + src + (int64_t)i * p.st);
         st16(p.Kr + dst + (int64_t)i * p.rt, kv);
         st16(p.Vr + dst + (int64_t)i * p.rt, vv);
     }
