@@ -9,8 +9,9 @@
 
 namespace tf {
 
-constexpr int kSumIters = 4;                          // chunk groups per wave
-constexpr int kSumChunksPerWg = 4 * 4 * kSumIters;    // 4 waves x 4 chunks x iters
+constexpr int kSumWaves = 2;                                  // waves per workgroup
+constexpr int kSumIters = 1;                                  // chunk groups per wave (1 measured best)
+constexpr int kSumChunksPerWg = kSumWaves * 4 * kSumIters;    // waves x 4 chunks x iters
 
 struct SumParams {
     const uint16_t *K;
@@ -22,7 +23,7 @@ struct SumParams {
     int64_t M_cap;
 };
 
-__global__ __launch_bounds__(256) void chunk_summarize_kernel(const SumParams p) {
+__global__ __launch_bounds__(kSumWaves * 64) void chunk_summarize_kernel(const SumParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, s = lane >> 4;
     const int64_t blk = blockIdx.x % p.blocks_per_bh;
@@ -88,7 +89,7 @@ int summarize_launch(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t
     p.Kmean = Kmean;
     p.M_cap = M_cap;
     if (p.blocks_per_bh * BH >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(chunk_summarize_kernel, dim3((unsigned)(p.blocks_per_bh * BH)), dim3(256), 0,
+    hipLaunchKernelGGL(chunk_summarize_kernel, dim3((unsigned)(p.blocks_per_bh * BH)), dim3(kSumWaves * 64), 0,
                        static_cast<hipStream_t>(stream), p);
     return hip_status(hipGetLastError());
 }
