@@ -399,3 +399,40 @@ def test_spec_accept_closed_form_identical_distributions():
     torch.cuda.synchronize()
     assert n.cpu().tolist() == [3] * 8
     assert torch.equal(out[:, :3].cpu(), a["draft_tokens"])
+
+
+# ----------------------------------------------------------------------------- maximum sizes
+def test_spec_accept_large_vocabulary_generic_path():
+    """A vocabulary beyond 32768 (and not a multiple of 4) takes the kernels' looping path."""
+    say("case spec_accept V=150001 seed=133")
+    check_accept(3, 3, 150001, 0.8, 133, correlated=True)
+    check_accept(2, 2, 150001, 0.0, 134, correlated=False)
+
+
+def test_topk_maximum_k_and_many_chunks():
+    """k = 2048 (the documented maximum) out of 65536 chunks, c = 1, no gather."""
+    say("case topk_max seed=124")
+    rng = np.random.default_rng(124)
+    B, H, M, k = 1, 2, 65536, tf.binding.TF_MAX_K_CHUNKS
+    km = rng.standard_normal((B, H, M, 128)).astype(np.float32)
+    q = bf16_u16(rng.standard_normal((B, H, 128)) * 0.3)
+    idx = torch.empty((B, H, k), dtype=torch.int32, device=DEV)
+    score = torch.empty((B, H, k), dtype=torch.float32, device=DEV)
+    K = torch.zeros((B, H, M, 128), dtype=torch.bfloat16, device=DEV)
+    tf.tf_chunk_topk_gather(u16_torch(q, DEV), torch.from_numpy(km).to(DEV), K, K, 1, k, idx, out_score=score)
+    torch.cuda.synchronize()
+    o_scores, o_idx = oracle.retrieve(q, km.astype(np.float64), k)
+    check_topk(idx.cpu().numpy(), score.cpu().numpy().astype(np.float64), o_scores, o_idx, [M], k, tag="max k")
+    with pytest.raises(tf.TfError):
+        tf.tf_chunk_topk_gather(u16_torch(q, DEV), torch.from_numpy(km).to(DEV), K, K, 1, k + 1,
+                                torch.empty((B, H, k + 1), dtype=torch.int32, device=DEV))
+
+
+def test_attn_eight_queries_many_splits():
+    say("case attn_G8_many_splits seed=108")
+    x = synth.make_layer(1, 2, 20000 + 9, 8, 8, 4, seed=108)
+    tf.tf_set_option("attn_full_tokens_per_split", 64)       # 313 splits per head
+    try:
+        check_attn(x, tf.tf_decode_attn_full, tag="G=8, 313 splits")
+    finally:
+        tf.tf_set_option("attn_full_tokens_per_split", 0)
