@@ -45,7 +45,8 @@ def test_workspace_queries(lib):
     retr = tf.tf_decode_attn_retrieval_workspace_bytes(1, 32, 4096, 3)
     assert 0 < retr < full < 64 << 20                  # partials stay far below the 2 GiB of KV per layer
     assert tf.tf_chunk_topk_gather_workspace_bytes(1, 32, 16384, 512) >= 32 * 16384 * 4
-    assert tf.tf_spec_accept_workspace_bytes(4, 5, 32000) == 4 * 9 * 16
+    seg = 8                                            # 32000 entries in segments of 4096
+    assert tf.tf_spec_accept_workspace_bytes(4, 5, 32000) == (4 * 9 * seg * 4 + 4 * seg * 1024 + 4 * seg) * 8
     assert tf.tf_decode_attn_full_workspace_bytes(0, 32, 10, 1) == 0
 
 
