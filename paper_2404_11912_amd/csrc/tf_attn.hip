@@ -420,17 +420,23 @@ static int num_cus() {
 static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, bool retrieval) {
     int64_t tps = retrieval ? g_tps_retr : g_tps_full;
     if (tps == 0) {
-        // The split kernel fits 3 workgroups (12 waves) per CU. Long caches: exactly one
-        // resident round of equal workgroups (measured best at 128K context: no tail, few
-        // partials). Short caches: more, smaller workgroups, but at least 128 tokens each.
+        // The split kernel fits 3 workgroups (12 waves) per CU. Long caches: one resident round
+        // of workgroups (measured best at 128K context: no tail, few partials), or, when the
+        // units do not divide the round, the next larger number of EQUAL splits -- a short last
+        // split that leaves part of the chip idle costs far more than a second partial round
+        // (10 sequences x 12K: 405 us with splits of 5120/5120/2048 tokens, 318 us with 3 x 4096).
+        // Short caches: more, smaller workgroups, but at least `min_tps` tokens each.
         const int64_t target_wgs = (int64_t)num_cus() * 3;
         const int64_t min_tps = retrieval ? 128 : 512;
-        tps = (kv_len_all * BH + target_wgs - 1) / target_wgs;
-        tps = ((tps + 63) / 64) * 64;
-        if (tps < min_tps) tps = min_tps;
+        int64_t ns = (target_wgs + BH - 1) / BH;
+        const int64_t ns_cap = kv_len_all / min_tps;
+        if (ns > ns_cap) ns = ns_cap;
+        if (ns > kMaxSplits) ns = kMaxSplits;  // the merge kernel stages one weight per split in LDS
+        if (ns < 1) ns = 1;
+        tps = (((kv_len_all + ns - 1) / ns + 63) / 64) * 64;
     }
     int64_t ns = (kv_len_all + tps - 1) / tps;
-    if (ns > kMaxSplits) {  // the merge kernel stages one weight per split in LDS
+    if (ns > kMaxSplits) {
         tps = (((kv_len_all + kMaxSplits - 1) / kMaxSplits + 63) / 64) * 64;
         ns = (kv_len_all + tps - 1) / tps;
     }

@@ -59,7 +59,8 @@ class Workload:
         return 2 * self.B * self.H * self.N * self.d * 2
 
 
-# The five configurations this build is specified on (index = position in that list).
+# The five configurations this build is specified on (index = position in that list), then
+# three more.
 WORKLOADS = {
     "tiny": Workload("tiny", 0, B=1, L=1, H=4, N=4096, c=8, R=512, G=5, V=1000, P=8),
     "layer32k": Workload("layer32k", 1, B=1, L=1, H=32, N=32768, c=8, R=4096, G=6, V=32000, P=64),
@@ -69,6 +70,14 @@ WORKLOADS = {
                           P=512),
     "batch4x64k": Workload("batch4x64k", 4, B=4, L=32, H=32, N=65536, c=8, R=4096, G=5, V=32000,
                            P=64),
+    # beyond the five: the batch shapes of the paper's batching table (Table 4: batch x context
+    # with the per-sequence retrieval budget it lists), same model shape
+    "batch2x56k": Workload("batch2x56k", 5, B=2, L=32, H=32, N=57344, c=8, R=1024, G=5, V=32000,
+                           P=64, temps=(0.0, 0.6)),
+    "batch6x19k": Workload("batch6x19k", 6, B=6, L=32, H=32, N=19456, c=8, R=768, G=5, V=32000,
+                           P=48, temps=(0.0, 0.6)),
+    "batch10x12k": Workload("batch10x12k", 7, B=10, L=32, H=32, N=12288, c=8, R=768, G=5, V=32000,
+                            P=48, temps=(0.0, 0.6)),
 }
 
 

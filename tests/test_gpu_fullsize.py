@@ -25,6 +25,7 @@ def say(msg):
     ("step128k", 0), ("step128k", 31),
     ("batch4x64k", 1),
     ("extreme1m", 1),
+    ("batch2x56k", 0), ("batch6x19k", 3), ("batch10x12k", 31),     # batch shapes of Table 4
 ])
 def test_one_layer_at_full_size(name, layer):
     w = synth.WORKLOADS[name]
@@ -132,3 +133,60 @@ def test_accept_batch4_vocab_32000(gamma):
     safe = (ma > 1e-9) & (ms > 1e-9)
     assert safe.all()
     assert np.array_equal(n.cpu().numpy(), n_o) and np.array_equal(out.cpu().numpy(), out_o)
+
+
+def test_batch_with_per_sequence_lengths_at_a_batching_shape():
+    """The 6 x 19K batch shape of Table 4 with six different context lengths (a ragged batch, one
+    of them not a multiple of the chunk or tile size): summaries, retrieval with per-sequence
+    chunk counts, draft and verification attention with per-sequence lengths, every unit."""
+    w = synth.WORKLOADS["batch6x19k"]
+    say("case fullsize ragged batch6x19k layer=1")
+    x = synth.make_workload_layer(w, 1, DEV)
+    K, V, Q, q_r = x["K"], x["V"], x["Q"], x["q_r"]
+    B, H, N, d = K.shape
+    lens = np.array([N, N - 8, 12345, 9000, 4099, 1024], dtype=np.int32)
+    ncs = (lens // w.c).astype(np.int32)
+    kv = torch.tensor(lens, device=DEV)
+    nc = torch.tensor(ncs, device=DEV)
+    Kmean = torch.empty((B, H, w.M, d), dtype=torch.float32, device=DEV)
+    tf.tf_chunk_summarize(K, w.c, Kmean, 0, w.M)
+    idx = torch.empty((B, H, w.k), dtype=torch.int32, device=DEV)
+    Kr = torch.zeros((B, H, w.R, d), dtype=torch.bfloat16, device=DEV)
+    Vr = torch.zeros_like(Kr)
+    tf.tf_chunk_topk_gather(q_r, Kmean, K, V, w.c, w.k, idx, Kr, Vr, n_chunks=nc, n_chunks_all=w.M)
+    O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+    L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_full(Q, K, V, O, L, kv_len=kv, kv_len_all=N, causal=True)
+    Qd = Q[:, :, -w.G_d:, :].contiguous()
+    O_d = torch.empty(Qd.shape, dtype=torch.float32, device=DEV)
+    L_d = torch.empty(Qd.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_indexed(Qd, K, V, idx, w.c, O_d, L_d, kv_len=kv, kv_len_all=N,
+                              recent_begin=kv - w.G_d, recent_begin_all=int(lens.min()) - w.G_d, causal=True)
+    torch.cuda.synchronize()
+    Ku, Vu, Qu = synth.as_u16(K), synth.as_u16(V), synth.as_u16(Q)
+    km = oracle.chunk_mean(Ku, w.c)
+    o_scores, o_idx = oracle.retrieve(synth.as_u16(q_r), km, w.k, n_chunks=ncs)
+    idx_h = idx.cpu().numpy()
+    same = np.zeros((B, H), dtype=bool)
+    for b in range(B):
+        for h in range(H):
+            s, got = o_scores[b, h][:ncs[b]], idx_h[b, h]
+            assert got.min() >= 0 and got.max() < ncs[b] and len(set(got.tolist())) == w.k
+            tau = s[o_idx[b, h, -1]]
+            assert set(np.where(s > tau + TIE_BAND)[0].tolist()) <= set(got.tolist())
+            assert not (set(got.tolist()) & set(np.where(s < tau - TIE_BAND)[0].tolist()))
+            assert np.all(s[got][1:] <= s[got][:-1] + TIE_BAND)
+            same[b, h] = np.array_equal(got, o_idx[b, h])
+    Oo, Lo, _ = oracle.attention(Qu, Ku, Vu, kv_len=lens, scale=1.0, causal=True)
+    e = float(np.max(np.abs(O.cpu().numpy() - Oo)))
+    el = float(np.max(np.abs(L.cpu().numpy() - Lo)))
+    say(f"[ragged 6x19k] verify attention: max|dO|={e:.2e} max|dLSE|={el:.2e}")
+    assert e <= ATTN_TOL and el <= LSE_TOL
+    # draft attention through the device's own indices (any valid selection defines a cache)
+    Od, Ld = oracle.attention_indexed(np.ascontiguousarray(Qu[:, :, -w.G_d:, :]), Ku, Vu, idx_h, w.c, kv_len=lens,
+                                      recent_begin=lens - w.G_d, scale=1.0, causal=True)[:2]
+    ed = float(np.max(np.abs(O_d.cpu().numpy() - Od)))
+    eld = float(np.max(np.abs(L_d.cpu().numpy() - Ld)))
+    say(f"[ragged 6x19k] indexed draft attention: max|dO|={ed:.2e} max|dLSE|={eld:.2e}; "
+        f"top-k order identical on {int(same.sum())}/{B * H} units")
+    assert ed <= ATTN_TOL and eld <= LSE_TOL
