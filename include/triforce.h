@@ -72,7 +72,8 @@ int tf_version(void);                   /* major*10000 + minor*100 + patch */
 const char *tf_status_string(int code); /* static string, never NULL */
 
 /* Tuning knobs (host state, not thread-safe against concurrent calls). Known names:
- *   "attn_full_tokens_per_split", "attn_retr_tokens_per_split"  (multiples of 64; 0 = auto).
+ *   "attn_full_tokens_per_split", "attn_retr_tokens_per_split"  (multiples of 64; 0 = auto),
+ *   "score_steps_per_wave" (16-chunk steps a wave of the scoring kernel takes; 0 = auto).
  * Returns TF_ERR_INVALID_ARG for an unknown name or bad value. Workspace queries reflect the
  * knobs in force when they are called. */
 int tf_set_option(const char *name, int64_t value);

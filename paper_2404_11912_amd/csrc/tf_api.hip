@@ -17,6 +17,7 @@ int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, co
 int kv_append_launch(const void *, const void *, int32_t, void *, void *, const tf_kv_desc *, const int32_t *,
                      int64_t, void *);
 int set_attn_option(bool retrieval, int64_t v);
+int set_score_option(int64_t v);
 size_t accept_workspace_bytes(int32_t, int32_t, int32_t);
 int accept_launch(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, float, const float *,
                   const float *, int32_t *, int32_t *, void *, size_t, void *);
@@ -41,6 +42,7 @@ int tf_set_option(const char *name, int64_t value) {
     if (!name) return TF_ERR_INVALID_ARG;
     if (!strcmp(name, "attn_full_tokens_per_split")) return tf::set_attn_option(false, value);
     if (!strcmp(name, "attn_retr_tokens_per_split")) return tf::set_attn_option(true, value);
+    if (!strcmp(name, "score_steps_per_wave")) return tf::set_score_option(value);
     return TF_ERR_INVALID_ARG;
 }
 

@@ -27,6 +27,10 @@ namespace tf {
 constexpr int kTile = 16;    // tokens per MFMA tile
 constexpr int kWaves = 4;    // waves per workgroup
 constexpr int kGPad = 8;     // query rows kept in the partials
+// tiles in flight per wave. Measured at 128K context, one workgroup per CU: depth 2 305 us,
+// depth 3 307 us, depth 4 307 us per layer -- the stream is not latency-bound, so the
+// shallowest pipeline (fewest registers) is used.
+constexpr int kPipeDepth = 2;
 
 struct AttnParams {
     const uint16_t *Q, *K, *V;
@@ -50,7 +54,7 @@ struct AttnParams {
 
 __device__ __forceinline__ float safe_max(float m) { return m == -INFINITY ? 0.0f : m; }
 
-template <bool kIndexed>
+template <bool kIndexed, int kDepth>
 __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -123,21 +127,25 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         return row;
     };
 
-    // loads of one tile; `rows` (indexed mode) is this lane's row for token t0+r, -1 = masked
-    auto load_k = [&](int t0, uint4(&k)[4], int &rows) {
+    // loads of one tile; `rows` (indexed mode) is this lane's row for token t0+r, -1 = masked.
+    // A tile that is not `live` (software-pipeline slots past the wave's last tile) is loaded
+    // from one fixed valid location with all lanes on the same 16 bytes, so the number of loads
+    // in flight never depends on control flow and the dummy costs one 64-byte request.
+    auto load_k = [&](int t0, bool live, uint4(&k)[4], int &rows) {
         if constexpr (kIndexed) {
-            rows = virtual_row(t0 + r);
+            rows = live ? virtual_row(t0 + r) : -1;
             const char *kp = Kb + (int64_t)max(rows, 0) * row_bytes + s * 16;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) k[kk] = ld16_stream(kp + kk * 64);
         } else {
-            const char *base = Kb + (int64_t)t0 * row_bytes;
+            const char *base = Kb + (int64_t)(live ? t0 : t_begin) * row_bytes;
+            const uint32_t off = live ? k_off : 0u;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16_stream(base + k_off + kk * 64);
+            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16_stream(base + off + kk * 64);
         }
     };
     // returns (indexed mode) the 4-bit validity mask of this lane's tokens 4s+i
-    auto load_v = [&](int t0, uint4(&v)[4], int rows) -> int {
+    auto load_v = [&](int t0, bool live, uint4(&v)[4], int rows) -> int {
         int vm = 0xf;
         if constexpr (kIndexed) {
             vm = 0;
@@ -148,9 +156,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
                 v[i] = ld16_stream(Vb + (int64_t)max(rv, 0) * row_bytes + r * 16);
             }
         } else {
-            const char *base = Vb + (int64_t)t0 * row_bytes;
+            const char *base = Vb + (int64_t)(live ? t0 : t_begin) * row_bytes;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = ld16_stream(base + v_off[i]);
+            for (int i = 0; i < 4; ++i) v[i] = ld16_stream(base + (live ? v_off[i] : 0u));
         }
         return vm;
     };
@@ -208,45 +216,36 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         }
     };
 
-    // 16-token tiles of this split, interleaved over the 4 waves. K of the next tile is
-    // requested before the current QK^T, V of the next tile right after it (when the current
-    // K registers are dead), so one tile of loads is always in flight per wave. Plain mode
-    // walks whole tiles here and leaves a ragged last tile to the clamped path below; indexed
-    // mode masks per token anyway, so the ragged tile is just one more tile.
+    // 16-token tiles of this split, interleaved over the 4 waves, in a software pipeline of
+    // kDepth tiles per wave: K of tile i+kDepth-1 is requested before the QK^T of tile i, its V
+    // right after (when the K registers of tile i are dead). Loads are never conditional (see
+    // load_k), so the wait counters stay exact. Plain mode walks whole tiles here and leaves a
+    // ragged last tile to the clamped path below; indexed mode masks per token anyway, so the
+    // ragged tile is just one more tile.
     const int n_full = kIndexed ? (t_end - t_begin + kTile - 1) / kTile : (t_end - t_begin) / kTile;
     const int n_mine_tiles = (n_full - wave + kWaves - 1) / kWaves;
     if (n_mine_tiles > 0) {
         constexpr int step = kWaves * kTile;
-        uint4 ka[4], va[4], kb2[4], vb2[4];
-        int ra = 0, rb2 = 0, ma = 0xf, mb = 0xf;
+        uint4 kb[kDepth][4], vb[kDepth][4];
+        int rws[kDepth], vms[kDepth];
         float z[4];
-        int t0 = t_begin + wave * kTile;
-        int left = n_mine_tiles;  // tiles not yet computed; buffer A always holds the next one
-        load_k(t0, ka, ra);
-        ma = load_v(t0, va, ra);
-        // steady state: no conditional loads, so the wait counters stay exact
-        while (left > 2) {
-            load_k(t0 + step, kb2, rb2);
-            qk_tile(ka, z);
-            mb = load_v(t0 + step, vb2, rb2);
-            softmax_pv(t0, z, va, ma);
-            load_k(t0 + 2 * step, ka, ra);
-            qk_tile(kb2, z);
-            ma = load_v(t0 + 2 * step, va, ra);
-            softmax_pv(t0 + step, z, vb2, mb);
-            t0 += 2 * step;
-            left -= 2;
+        const int t_first = t_begin + wave * kTile;
+#pragma unroll
+        for (int j = 0; j < kDepth - 1; ++j) {
+            load_k(t_first + j * step, j < n_mine_tiles, kb[j], rws[j]);
+            vms[j] = load_v(t_first + j * step, j < n_mine_tiles, vb[j], rws[j]);
         }
-        if (left == 2) {
-            load_k(t0 + step, kb2, rb2);
-            qk_tile(ka, z);
-            mb = load_v(t0 + step, vb2, rb2);
-            softmax_pv(t0, z, va, ma);
-            qk_tile(kb2, z);
-            softmax_pv(t0 + step, z, vb2, mb);
-        } else {
-            qk_tile(ka, z);
-            softmax_pv(t0, z, va, ma);
+        for (int i = 0; i < n_mine_tiles; i += kDepth) {
+#pragma unroll
+            for (int j = 0; j < kDepth; ++j) {
+                const int nb = (j + kDepth - 1) % kDepth;   // buffer freed by the previous tile
+                const int nxt = i + j + kDepth - 1;
+                const bool cur_live = i + j < n_mine_tiles;
+                load_k(t_first + nxt * step, nxt < n_mine_tiles, kb[nb], rws[nb]);
+                if (cur_live) qk_tile(kb[j], z);
+                vms[nb] = load_v(t_first + nxt * step, nxt < n_mine_tiles, vb[nb], rws[nb]);
+                if (cur_live) softmax_pv(t_first + (i + j) * step, z, vb[j], vms[j]);
+            }
         }
     }
     // plain mode, ragged tail (len not a multiple of 16): one partial tile, rows clamped to the
@@ -417,23 +416,55 @@ static int num_cus() {
     return cached;
 }
 
-static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, bool retrieval) {
+// Split planning. Measured on MI355X with streaming (nt) loads: the fewer workgroups stream
+// concurrently, the higher the HBM bandwidth, as long as every CU has one -- at 128K context one
+// workgroup per CU reads 7.05 TB/s, two per CU 6.90, three per CU 6.70 (fewer DRAM streams in
+// flight); a count that leaves CUs with unequal numbers of workgroups is far worse (1.5 per CU:
+// 5.7 TB/s), and so are unequal splits. The plan therefore takes, among the split counts whose
+// splits are equal, the one with the smallest modelled time
+//     (workgroups on the busiest CU) x (tokens per split) / rate(workgroups per CU),
+// which is "one workgroup per CU" whenever batch x heads divides the CU count.
+// The indexed form chases an index before every row (a dependent load), so it is latency-bound and
+// wants the opposite: three workgroups per CU (19 us against 23.5 us per layer at a 4K budget).
+enum PlanMode { kPlanFull = 0, kPlanRetrieval = 1, kPlanIndexed = 2 };
+
+static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
+    const bool retrieval = mode != kPlanFull;
     int64_t tps = retrieval ? g_tps_retr : g_tps_full;
     if (tps == 0) {
-        // The split kernel fits 3 workgroups (12 waves) per CU. Long caches: one resident round
-        // of workgroups (measured best at 128K context: no tail, few partials), or, when the
-        // units do not divide the round, the next larger number of EQUAL splits -- a short last
-        // split that leaves part of the chip idle costs far more than a second partial round
-        // (10 sequences x 12K: 405 us with splits of 5120/5120/2048 tokens, 318 us with 3 x 4096).
-        // Short caches: more, smaller workgroups, but at least `min_tps` tokens each.
-        const int64_t target_wgs = (int64_t)num_cus() * 3;
-        const int64_t min_tps = retrieval ? 128 : 512;
-        int64_t ns = (target_wgs + BH - 1) / BH;
-        const int64_t ns_cap = kv_len_all / min_tps;
-        if (ns > ns_cap) ns = ns_cap;
-        if (ns > kMaxSplits) ns = kMaxSplits;  // the merge kernel stages one weight per split in LDS
-        if (ns < 1) ns = 1;
-        tps = (((kv_len_all + ns - 1) / ns + 63) / 64) * 64;
+        struct Memo {
+            int64_t BH, len;
+            int64_t tps;
+        };
+        static thread_local Memo memo[3] = {{0, 0, 0}, {0, 0, 0}, {0, 0, 0}};
+        Memo &mm = memo[mode];
+        if (mm.BH == BH && mm.len == kv_len_all) {
+            tps = mm.tps;
+        } else {
+            const int64_t cus = num_cus();
+            const int64_t min_tps = retrieval ? 128 : 512;  // shorter splits are all overhead
+            int64_t ns_cap = kv_len_all / min_tps;
+            if (ns_cap > kMaxSplits) ns_cap = kMaxSplits;   // the merge kernel stages one weight per split
+            const int64_t ns_useful = (8 * cus + BH - 1) / BH;  // beyond 8 workgroups per CU nothing changes
+            if (ns_cap > ns_useful) ns_cap = ns_useful;
+            if (ns_cap < 1) ns_cap = 1;
+            double best = 0.0;
+            for (int64_t ns = 1; ns <= ns_cap; ++ns) {
+                const int64_t t = (((kv_len_all + ns - 1) / ns + 63) / 64) * 64;
+                const int64_t n_eff = (kv_len_all + t - 1) / t;
+                const int64_t per_cu = (BH * n_eff + cus - 1) / cus;
+                const double rate = mode == kPlanIndexed ? (per_cu <= 1 ? 0.80 : (per_cu == 2 ? 0.95 : 1.0))
+                                                         : (per_cu <= 1 ? 1.0 : (per_cu == 2 ? 0.982 : 0.955));
+                const double cost = (double)per_cu * (double)t / rate;
+                if (ns == 1 || cost < best * (1.0 - 1e-9)) {
+                    best = cost;
+                    tps = t;
+                }
+            }
+            mm.BH = BH;
+            mm.len = kv_len_all;
+            mm.tps = tps;
+        }
     }
     int64_t ns = (kv_len_all + tps - 1) / tps;
     if (ns > kMaxSplits) {
@@ -451,7 +482,7 @@ static size_t attn_ws_bytes(int64_t BH, const SplitPlan &sp) {
 size_t attn_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G, bool retrieval) {
     if (batch <= 0 || heads <= 0 || kv_len_all <= 0 || G <= 0) return 0;
     const int64_t BH = (int64_t)batch * heads;
-    return attn_ws_bytes(BH, plan_splits(BH, kv_len_all, retrieval));
+    return attn_ws_bytes(BH, plan_splits(BH, kv_len_all, retrieval ? kPlanRetrieval : kPlanFull));
 }
 
 
@@ -465,7 +496,7 @@ size_t attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chun
     const int64_t lv = (int64_t)k_chunks * chunk + recent_len_all;
     if (lv <= 0) return 0;
     const int64_t BH = (int64_t)batch * heads;
-    return attn_ws_bytes(BH, plan_splits(BH, lv, true));
+    return attn_ws_bytes(BH, plan_splits(BH, lv, kPlanIndexed));
 }
 
 int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
@@ -492,7 +523,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     if (!(scale == scale) || scale - scale != 0.f) return TF_ERR_INVALID_ARG;  // NaN or infinite
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return TF_ERR_INVALID_ARG;
     const int64_t BH = (int64_t)kd->batch * kd->heads;
-    const SplitPlan sp = plan_splits(BH, plan_len, retrieval);
+    const SplitPlan sp = plan_splits(BH, plan_len, ix ? kPlanIndexed : (retrieval ? kPlanRetrieval : kPlanFull));
     if (BH * sp.nsplit >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
     if (!ws || !aligned(ws, 256) || ws_bytes < attn_ws_bytes(BH, sp)) return TF_ERR_WORKSPACE;
 
@@ -523,9 +554,9 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(BH * sp.nsplit));
     if (ix)
-        hipLaunchKernelGGL(attn_split_kernel<true>, grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth>), grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(attn_split_kernel<false>, grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth>), grid, dim3(256), 0, st, p);
     hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(BH * G)), dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
                        sp.nsplit, G, O, LSE);
     return hip_status(hipGetLastError());

@@ -3,8 +3,8 @@
 //
 // Three kernels on one stream:
 //   score   HBM streaming over the fp32 average-key table (512 B per chunk). A wave takes 16
-//           chunk rows at a time; lane (r,s) holds dims {16j+4s..+4} of row r, does 32 fp32
-//           FMAs against the resident query and two wave shuffles finish the dot product.
+//           chunk rows at a time, 8 lanes per row reading whole 128-byte lines; 32 fp32 FMAs
+//           per lane against the resident query, three shuffles per row finish the dot product.
 //   select  one 1024-thread workgroup per (b,h): exact radix select (4 x 8 bits, LDS
 //           histograms) of the k-th largest order-preserving key, ordered compaction of the
 //           winners (ties toward the lower chunk index), bitonic sort of the <= 2048 winners
@@ -15,9 +15,15 @@
 
 namespace tf {
 
-constexpr int kScoreIters = 4;
-constexpr int kScoreRowsPerWg = 4 * 16 * kScoreIters;  // 4 waves x 16 rows x iters
+constexpr int kScoreMaxIters = 16;  // 16-row steps per wave (a workgroup covers 4 x 16 x iters rows)
 constexpr int kSelThreads = 1024;
+static int64_t g_score_iters = 0;  // 0 = automatic
+
+int set_score_option(int64_t v) {
+    if (v < 0 || v > 4096) return TF_ERR_INVALID_ARG;
+    g_score_iters = v;
+    return TF_OK;
+}
 
 struct ScoreParams {
     const uint16_t *q_r;
@@ -25,50 +31,97 @@ struct ScoreParams {
     int64_t M_cap;
     const int32_t *n_chunks;
     int32_t n_all, H;
-    int32_t blocks_per_bh;
+    int32_t blocks_per_bh, iters;
     float *scores;
     int64_t score_stride;
 };
 
+// Every load instruction of a wave reads 8 rows x 128 contiguous bytes (whole cache lines:
+// 64-byte pieces stream about 9% slower): lane (e, w) = (lane % 8, lane / 8) holds dims
+// {32j + 4e .. +4}, j < 4, of row w, does 16 fp32 FMAs against the resident query and three
+// shuffles over the 8 lanes of a row finish the dot product. The next step's loads are in flight
+// while the current one is reduced.
 __global__ __launch_bounds__(256) void chunk_score_kernel(const ScoreParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 15, s = lane >> 4;
+    const int e = lane & 7, w = lane >> 3;
     const int blk = blockIdx.x % p.blocks_per_bh;
     const int64_t bh = blockIdx.x / p.blocks_per_bh;
     const int b = (int)(bh / p.H);
     int n = p.n_chunks ? p.n_chunks[b] : p.n_all;
     n = min(max(n, 0), p.n_all);
+    const int last_row = max(n - 1, 0);
 
-    float q[8][4];
+    float q[4][4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint2 w = *reinterpret_cast<const uint2 *>(p.q_r + bh * kHeadDim + 16 * j + 4 * s);
-        q[j][0] = bf16lo(w.x);
-        q[j][1] = bf16hi(w.x);
-        q[j][2] = bf16lo(w.y);
-        q[j][3] = bf16hi(w.y);
+    for (int j = 0; j < 4; ++j) {
+        const uint2 u = *reinterpret_cast<const uint2 *>(p.q_r + bh * kHeadDim + 32 * j + 4 * e);
+        q[j][0] = bf16lo(u.x);
+        q[j][1] = bf16hi(u.x);
+        q[j][2] = bf16lo(u.y);
+        q[j][3] = bf16hi(u.y);
     }
-    const float *base = p.Kmean + bh * p.M_cap * kHeadDim + 4 * s;
-#pragma unroll 1
-    for (int it = 0; it < kScoreIters; ++it) {
-        const int m = blk * kScoreRowsPerWg + (wave * kScoreIters + it) * 16 + r;
-        if (blk * kScoreRowsPerWg + (wave * kScoreIters + it) * 16 >= p.n_all) break;  // wave-uniform
-        const int m_ld = min(m, max(n - 1, 0));
-        const float *row = base + (int64_t)m_ld * kHeadDim;
-        float4 v[8];
+    const float *base = p.Kmean + bh * p.M_cap * kHeadDim + 4 * e;
+    float *out = p.scores + bh * p.score_stride;
+
+    // the 4 waves interleave 16-row steps over the workgroup's contiguous range (one stream
+    // per workgroup, as in the attention kernel)
+    const int m_begin = blk * 64 * p.iters + wave * 16;
+    const int m_end = min((blk + 1) * 64 * p.iters, p.n_all);
+    int left = (m_end - m_begin + 63) / 64;  // 16-row steps of this wave
+
+    // rows past the sequence's chunk count are clamped to its last row (read, never stored)
+    auto load = [&](int m0, float4(&v)[8]) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = ldf4_stream(row + 16 * j);
-        float acc = 0.f;
+        for (int rr = 0; rr < 2; ++rr) {
+            const float *row = base + (int64_t)min(m0 + 8 * rr + w, last_row) * kHeadDim;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            acc = fmaf(q[j][0], v[j].x, acc);
-            acc = fmaf(q[j][1], v[j].y, acc);
-            acc = fmaf(q[j][2], v[j].z, acc);
-            acc = fmaf(q[j][3], v[j].w, acc);
+            for (int j = 0; j < 4; ++j) v[4 * rr + j] = ldf4_stream(row + 32 * j);
         }
-        acc += __shfl_xor(acc, 16, kWave);
-        acc += __shfl_xor(acc, 32, kWave);
-        if (s == 0 && m < p.n_all) p.scores[bh * p.score_stride + m] = m < n ? acc : -INFINITY;
+    };
+    auto finish = [&](int m0, const float4(&v)[8]) {
+        float acc[2];
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+            float a = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                a = fmaf(q[j][0], v[4 * rr + j].x, a);
+                a = fmaf(q[j][1], v[4 * rr + j].y, a);
+                a = fmaf(q[j][2], v[4 * rr + j].z, a);
+                a = fmaf(q[j][3], v[4 * rr + j].w, a);
+            }
+            a += __shfl_xor(a, 1, kWave);
+            a += __shfl_xor(a, 2, kWave);
+            a += __shfl_xor(a, 4, kWave);
+            acc[rr] = a;
+        }
+        // lanes e = 0 / e = 1 store rows m0 + w / m0 + 8 + w. (These few stores cost 15% of the
+        // stream's bandwidth -- 7.1 -> 6.2 TB/s in isolation -- whether written per step or
+        // collected in LDS and written as one 4 KiB burst per workgroup; only scores that never
+        // leave the L2 are free, so the simple form stays.)
+        const int m = m0 + 8 * e + w;
+        if (e < 2 && m < p.n_all) out[m] = m < n ? (e == 0 ? acc[0] : acc[1]) : -INFINITY;
+    };
+
+    if (left > 0) {
+        float4 va[8], vb[8];
+        int m0 = m_begin;
+        load(m0, va);
+        while (left > 2) {
+            load(m0 + 64, vb);
+            finish(m0, va);
+            load(m0 + 128, va);
+            finish(m0 + 64, vb);
+            m0 += 128;
+            left -= 2;
+        }
+        if (left == 2) {
+            load(m0 + 64, vb);
+            finish(m0, va);
+            finish(m0 + 64, vb);
+        } else {
+            finish(m0, va);
+        }
     }
 }
 
@@ -309,7 +362,13 @@ int topk_gather_launch(const void *q_r, const float *Kmean, int64_t M_cap, const
     sp.n_chunks = n_chunks;
     sp.n_all = (int32_t)n_chunks_all;
     sp.H = kd->heads;
-    sp.blocks_per_bh = (int32_t)((n_chunks_all + kScoreRowsPerWg - 1) / kScoreRowsPerWg);
+    // steps per wave: long tables give every workgroup up to 1024 rows (512 KiB), short ones
+    // keep at least ~2048 workgroups in the launch
+    int64_t iters = n_chunks_all * BH / (64 * 2048);
+    iters = iters < 1 ? 1 : (iters > kScoreMaxIters ? kScoreMaxIters : iters);
+    if (g_score_iters > 0) iters = g_score_iters;
+    sp.iters = (int32_t)iters;
+    sp.blocks_per_bh = (int32_t)((n_chunks_all + 64 * iters - 1) / (64 * iters));
     sp.scores = static_cast<float *>(ws);
     sp.score_stride = score_stride_of(n_chunks_all);
     if (sp.blocks_per_bh * BH >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
