@@ -139,6 +139,16 @@ class Step:
                                        self.layer(self.LSE_d, l), kv_len_all=w.N, recent_begin_all=w.N - w.G_d,
                                        scale=1.0, causal=True, ws=self.ws)
 
+    def tree_pass(self):
+        """Verification attention of all layers for a 7-node binary token tree (parents 0,0,1,1,2,2)."""
+        masks = [0b0000001, 0b0000011, 0b0000101, 0b0001011, 0b0010011, 0b0100101, 0b1000101]
+        if not hasattr(self, "Q_t"):
+            self.Q_t = self.Q[:, :, -1:, :].expand(-1, -1, 7, -1).contiguous()
+            self.O_t = torch.empty(self.Q_t.shape, dtype=torch.float32, device=self.dev)
+        for l in range(self.L):
+            self.tf.tf_decode_attn_tree(self.layer(self.Q_t, l), self.layer(self.K, l), self.layer(self.V, l),
+                                        masks, self.layer(self.O_t, l), scale=1.0, ws=self.ws)
+
     def accept(self, a):
         self.tf.tf_spec_accept(a["target_logits"], a["draft_logits"], a["draft_tokens"], self.T,
                                a["u_accept"], a["u_sample"], a["n"], a["out"], ws=self.ws)
@@ -275,6 +285,12 @@ def main():
     ev = [_timed(lambda: [step.draft_attn_indexed(l) for l in range(L)]) for _ in range(3)]
     torch.cuda.synchronize()
     indexed_us = float(np.mean([a.elapsed_time(b) for a, b in ev])) * 1e3
+    # ... and a verification pass over a 7-node binary token tree instead of the chain
+    step.tree_pass()
+    torch.cuda.synchronize()
+    ev = [_timed(step.tree_pass) for _ in range(3)]
+    torch.cuda.synchronize()
+    tree_us = float(np.mean([a.elapsed_time(b) for a, b in ev])) * 1e3
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
@@ -303,7 +319,8 @@ def main():
         "breakdown_us_per_step": breakdown,
         "one_time": {"chunk_summarize_all_layers_us": round(summarize_all_us, 1),
                      "chunk_summarize_gbps": round(summ_bytes / summarize_all_us / 1e3, 1)},
-        "extra": {"decode_attn_indexed_us_per_step": round(indexed_us, 1)},
+        "extra": {"decode_attn_indexed_us_per_step": round(indexed_us, 1),
+                  "decode_attn_tree7_us_per_step": round(tree_us, 1)},
         "roofline": {"bound": "hbm", "kernel": "attn_split_kernel (tf_decode_attn_full)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),

@@ -17,6 +17,9 @@
  * and, beyond those five, the cache-update pieces of Sec. 4.3:
  *   tf_decode_attn_indexed    drafting through the chunk indices, no gathered copy
  *   tf_kv_append              write new tokens' K/V rows into a cache
+ * and the verification pass for a token tree instead of a chain (Sec. 5.3.3, compatibility with
+ * tree-based speculative decoding):
+ *   tf_decode_attn_tree       tf_decode_attn_full with a per-query mask over the speculated tokens
  *
  * Conventions (all calls)
  *   - Every data pointer is a DEVICE pointer owned by the caller (the only host pointers are
@@ -137,6 +140,24 @@ size_t tf_decode_attn_full_workspace_bytes(int32_t batch, int32_t heads, int64_t
 int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
                         const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
                         int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes,
+                        void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_decode_attn_tree -- verification of a speculated token TREE (Sec. 5.3.3 "Compatibility with
+ * Tree-based Speculative Decoding"): tf_decode_attn_full with the causal triangle replaced by an
+ * ancestor mask. The G speculated tokens are the last G rows of the cache, in any order that
+ * puts parents before children; query g sees every row t < len[b]-G (the context) and, of the
+ * speculated rows, row len[b]-G+j iff bit j of tail_mask[g] is set (normally its ancestors and
+ * itself). tail_mask[g] = (2 << g) - 1 reproduces causal != 0, 0xff reproduces causal == 0.
+ *   tail_mask  in  HOST array of G bytes, read during the call (the only host-side input);
+ *                  bits >= G are ignored.
+ * Other arguments, outputs, limits, workspace size and errors as tf_decode_attn_full
+ * (tf_decode_attn_full_workspace_bytes); requires kv_len_all >= G. A query that sees nothing
+ * gets O = 0, LSE = -inf.
+ * ------------------------------------------------------------------------------------- */
+int tf_decode_attn_tree(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                        const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
+                        const uint8_t *tail_mask, float *O, float *LSE, void *ws, size_t ws_bytes,
                         void *stream);
 
 /* ---------------------------------------------------------------------------------------

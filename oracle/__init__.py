@@ -7,6 +7,7 @@ from .tf_oracle import (  # noqa: F401
     accept,
     attention,
     attention_indexed,
+    attention_tree,
     build_oracle,
     chunk_mean,
     gather,

@@ -180,6 +180,36 @@ def attention_indexed(Q, K, V, idx, c: int, kv_len=None, recent_begin=None, scal
     return O, LSE
 
 
+def attention_tree(Q, K, V, tail_mask, kv_len=None, scale: float = 1.0):
+    """Verification attention for a speculated token tree (Sec. 5.3.3), written as its definition:
+    the G speculated tokens are the last G rows of each sequence; query g attends to the context
+    rows [0, len-G) and to speculated row len-G+j iff bit j of tail_mask[g] is set. For every
+    (b, g) the visible rows are collected explicitly and the plain (unmasked) attention of that one
+    query over them is computed by the C routine.
+    Q [B,H,G,d], K,V [B,H,N,d] uint16(bf16), tail_mask G ints -> (O, LSE) float64."""
+    Q, K, V = _u16(Q), _u16(K), _u16(V)
+    B, H, G, d = Q.shape
+    N = K.shape[2]
+    kv = np.broadcast_to(np.asarray(N if kv_len is None else kv_len, dtype=np.int64), (B,))
+    mask = [int(m) for m in tail_mask]
+    assert len(mask) == G
+    O = np.zeros((B, H, G, d), dtype=np.float64)
+    LSE = np.full((B, H, G), -np.inf, dtype=np.float64)
+    for b in range(B):
+        n = int(kv[b])
+        ctx = np.arange(max(n - G, 0))
+        for g in range(G):
+            tail = [n - G + j for j in range(G) if (mask[g] >> j) & 1 and n - G + j >= 0]
+            rows = np.concatenate([ctx, np.asarray(tail, dtype=np.int64)]).astype(np.int64)
+            if rows.size == 0:
+                continue
+            Kv = np.ascontiguousarray(K[b][:, rows])[None]
+            Vv = np.ascontiguousarray(V[b][:, rows])[None]
+            o, l, _ = attention(np.ascontiguousarray(Q[b:b + 1, :, g:g + 1]), Kv, Vv, scale=scale, causal=False)
+            O[b, :, g], LSE[b, :, g] = o[0, :, 0], l[0, :, 0]
+    return O, LSE
+
+
 def kv_append(Knew, Vnew, K, V, pos):
     """Cache update (Algorithm 1, "Update C_r, C_q"; Sec. 4.3): returns copies of K, V with
     K[b,h,pos[b]+i] = Knew[b,h,i] (same for V); destination rows outside the cache are dropped."""

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     tf_decode_attn_indexed,
     tf_decode_attn_indexed_workspace_bytes,
     tf_kv_append,
+    tf_decode_attn_tree,
     tf_decode_attn_full_workspace_bytes,
     tf_decode_attn_retrieval,
     tf_decode_attn_retrieval_workspace_bytes,

@@ -27,6 +27,7 @@ EXPORTS = (
     "tf_decode_attn_retrieval_workspace_bytes", "tf_decode_attn_retrieval",
     "tf_spec_accept_workspace_bytes", "tf_spec_accept",
     "tf_decode_attn_indexed_workspace_bytes", "tf_decode_attn_indexed", "tf_kv_append",
+    "tf_decode_attn_tree",
 )
 
 
@@ -79,6 +80,9 @@ def load_library() -> ctypes.CDLL:
     lib.tf_decode_attn_indexed.restype = ctypes.c_int
     lib.tf_decode_attn_indexed.argtypes = [vp, vp, vp, dp, vp, i32, i32, vp, i64, vp, i64, i32, f32, i32, vp, vp,
                                            vp, sz, vp]
+    lib.tf_decode_attn_tree.restype = ctypes.c_int
+    lib.tf_decode_attn_tree.argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, ctypes.POINTER(ctypes.c_uint8), vp, vp, vp,
+                                        sz, vp]
     lib.tf_kv_append.restype = ctypes.c_int
     lib.tf_kv_append.argtypes = [vp, vp, i32, vp, vp, dp, vp, i64, vp]
     lib.tf_spec_accept_workspace_bytes.restype = sz
@@ -189,7 +193,7 @@ def tf_chunk_topk_gather(q_r, Kmean, K, V, chunk: int, k_chunks: int, out_idx, K
     return out_idx
 
 
-def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream):
+def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream, tail_mask=None):
     lib = load_library()
     _need(Q, torch.bfloat16, "Q")
     _need(O, torch.float32, "O")
@@ -211,10 +215,18 @@ def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream):
     if kv_len_all is None:
         kv_len_all = K.shape[2]
     if ws is None:
-        nbytes = getattr(lib, name + "_workspace_bytes")(d.batch, d.heads, int(kv_len_all), int(G))
+        ws_name = "tf_decode_attn_full" if tail_mask is not None else name
+        nbytes = getattr(lib, ws_name + "_workspace_bytes")(d.batch, d.heads, int(kv_len_all), int(G))
         ws = workspace(nbytes, K.device)
+    if tail_mask is not None:
+        rows = [int(m) for m in tail_mask]
+        if len(rows) != G or any(m < 0 or m > 255 for m in rows):
+            raise ValueError("tail_mask must hold G values in [0, 255]")
+        mask_arg = (ctypes.c_uint8 * G)(*rows)            # host array, read during the call
+    else:
+        mask_arg = int(bool(causal))
     _check(name, getattr(lib, name)(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(kv_len), int(kv_len_all),
-                                    int(G), float(scale), int(bool(causal)), _ptr(O), _ptr(LSE), _ptr(ws),
+                                    int(G), float(scale), mask_arg, _ptr(O), _ptr(LSE), _ptr(ws),
                                     ws.numel() * ws.element_size(), _stream(stream)))
     return O
 
@@ -231,6 +243,14 @@ def tf_decode_attn_full(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None, scal
                         causal: bool = True, ws=None, stream=None):
     """Verification attention: G queries [B,H,G,d] over the full cache K,V [B,H,N,d] -> O fp32, LSE fp32."""
     return _attn("tf_decode_attn_full", Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream)
+
+
+def tf_decode_attn_tree(Q, K, V, tail_mask, O, LSE=None, kv_len=None, kv_len_all=None, scale: float = 1.0,
+                        ws=None, stream=None):
+    """Verification attention for a token tree: tail_mask[g] bit j = query g sees speculated token j
+    (the last G cache rows); every query sees the rows before them."""
+    return _attn("tf_decode_attn_tree", Q, K, V, O, LSE, kv_len, kv_len_all, scale, False, ws, stream,
+                 tail_mask=tail_mask)
 
 
 def tf_decode_attn_retrieval(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None, scale: float = 1.0,

@@ -37,7 +37,12 @@ struct AttnParams {
     int64_t sb, sh, st;
     const int32_t *kv_len;
     int32_t kv_len_all;  // plain: upper bound of the cache length; indexed: of the virtual length
-    int32_t H, G, causal;
+    int32_t H, G;
+    // masked != 0: the last G tokens of the sequence are the queries' own; query g sees the
+    // tokens before them and the j-th of them iff bit j of byte g of tail_mask is set (causal:
+    // bits 0..g; a token tree: the node's ancestors and itself). masked == 0: every query sees all.
+    int32_t masked;
+    uint64_t tail_mask;
     int32_t nsplit, tokens_per_split;
     float scale_log2;
     float *part_o;   // [BH][nsplit][kGPad][128]
@@ -105,9 +110,10 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     }
     __syncthreads();
 
-    // tokens < n_all are visible to every query; this lane's query sees tokens < n_mine
-    const int n_all = p.causal ? len - p.G + 1 : len;
-    const int n_mine = (p.causal && r < p.G) ? len - p.G + 1 + r : len;
+    // tokens < n_all are visible to every query; of the last G tokens this lane's query sees
+    // those whose bit is set in my_mask
+    const int n_all = p.masked ? len - p.G : len;
+    const uint32_t my_mask = (uint32_t)(p.tail_mask >> (8 * (r & 7))) & 0xffu;  // this lane's query
 
     f32x4_t o[8];
 #pragma unroll
@@ -182,8 +188,11 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     auto softmax_pv = [&](int t0, float(&z)[4], const uint4(&v)[4], int vm) {
         if (kIndexed || t0 + kTile > n_all) {  // wave-uniform: tiles touching the causal / ragged tail
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (t0 + 4 * s + i >= n_mine || !((vm >> i) & 1)) z[i] = -INFINITY;
+            for (int i = 0; i < 4; ++i) {
+                const int t = t0 + 4 * s + i;
+                const bool visible = t < n_all || (t < len && ((my_mask >> ((t - n_all) & 31)) & 1u));
+                if (!visible || !((vm >> i) & 1)) z[i] = -INFINITY;
+            }
         }
         float mt = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
         mt = wave_max_xor(mt, 16);
@@ -501,7 +510,7 @@ size_t attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chun
 
 int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
                 int64_t kv_len_all, int32_t G, float scale, int32_t causal, float *O, float *LSE, void *ws,
-                size_t ws_bytes, void *stream, bool retrieval, const IndexedArgs *ix) {
+                size_t ws_bytes, void *stream, bool retrieval, const IndexedArgs *ix, const uint8_t *tail_mask) {
     if (!Q || !K || !V || !O) return TF_ERR_INVALID_ARG;
     int rc = check_desc(kd);
     if (rc != TF_OK) return rc;
@@ -519,7 +528,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
         if (plan_len < 1) return TF_ERR_INVALID_ARG;
         if (plan_len > (int64_t)1 << 30) return TF_ERR_UNSUPPORTED;
     }
-    if (causal && plan_len < G) return TF_ERR_INVALID_ARG;
+    if ((causal || tail_mask) && plan_len < G) return TF_ERR_INVALID_ARG;
     if (!(scale == scale) || scale - scale != 0.f) return TF_ERR_INVALID_ARG;  // NaN or infinite
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return TF_ERR_INVALID_ARG;
     const int64_t BH = (int64_t)kd->batch * kd->heads;
@@ -538,7 +547,12 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.kv_len_all = (int32_t)plan_len;
     p.H = kd->heads;
     p.G = G;
-    p.causal = causal ? 1 : 0;
+    p.masked = (causal || tail_mask) ? 1 : 0;
+    p.tail_mask = 0;
+    for (int g = 0; g < G; ++g) {
+        const uint32_t row = tail_mask ? (tail_mask[g] & ((1u << G) - 1u)) : ((2u << g) - 1u);
+        p.tail_mask |= (uint64_t)row << (8 * g);
+    }
     p.nsplit = sp.nsplit;
     p.tokens_per_split = sp.tokens_per_split;
     p.scale_log2 = scale * kLog2e;

@@ -50,6 +50,27 @@ def test_workspace_queries(lib):
     assert tf.tf_decode_attn_full_workspace_bytes(0, 32, 10, 1) == 0
 
 
+def _nsplit(fn, B, H, N, G):
+    return fn(B, H, N, G) // (B * H * (8 * 128 + 16) * 4)          # partials: 8 rows x (128 + 2) floats per split
+
+
+def test_split_planning(lib):
+    """Without a GPU the planner assumes 256 CUs. Long caches whose units divide the CU count get
+    one workgroup per CU; others get equal splits on a whole number of workgroups per CU."""
+    full, retr = tf.tf_decode_attn_full_workspace_bytes, tf.tf_decode_attn_retrieval_workspace_bytes
+    assert _nsplit(full, 1, 32, 131072, 5) == 8
+    assert _nsplit(full, 1, 32, 1048576, 5) == 8
+    assert _nsplit(full, 4, 32, 65536, 5) == 2
+    assert _nsplit(full, 2, 32, 57344, 5) == 4
+    assert _nsplit(full, 6, 32, 19456, 5) == 4                      # 768 workgroups: three per CU
+    assert _nsplit(full, 10, 32, 12288, 5) == 4
+    assert _nsplit(retr, 1, 32, 4096, 3) == 8
+    assert _nsplit(full, 1, 1, 3, 3) == 1                           # never more splits than 512-token pieces
+    assert _nsplit(full, 1, 4, 4096, 5) == 8
+    assert _nsplit(full, 1, 1, 1 << 30, 8) <= 2048                  # the merge kernel's limit
+    assert tf.tf_decode_attn_indexed_workspace_bytes(1, 32, 512, 8, 3, 3) // (32 * (8 * 128 + 16) * 4) == 22
+
+
 def test_options(lib):
     tf.tf_set_option("attn_full_tokens_per_split", 256)
     small = tf.tf_decode_attn_full_workspace_bytes(1, 1, 4096, 4)
@@ -71,6 +92,10 @@ def test_host_side_argument_checks(lib):
     assert lib.tf_decode_attn_full(None, p, p, ref(d), None, 64, 4, 1.0, 1, p, None, p, 1 << 20, None) == -1
     assert lib.tf_chunk_summarize(None, ref(d), 8, 0, 8, p, 8, None) == -1
     assert lib.tf_spec_accept(None, p, p, 1, 2, 10, 1.0, p, p, p, p, p, 1 << 10, None) == -1
+    assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 64, 4, 1.0, None, p, None, p, 1 << 20, None) == -1
+    m4 = (ctypes.c_uint8 * 4)(1, 3, 5, 9)
+    assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 3, 4, 1.0, m4, p, None, p, 1 << 20, None) == -1   # fewer rows than G
+    assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 64, 4, 1.0, m4, p, None, p, 16, None) == -3
     # unsupported shapes
     assert lib.tf_decode_attn_full(p, p, p, ref(bad_dim), None, 64, 4, 1.0, 1, p, None, p, 1 << 20, None) == -2
     assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 64, 9, 1.0, 1, p, None, p, 1 << 20, None) == -2
