@@ -30,7 +30,10 @@
  *     *_workspace_bytes() query returns (256-byte aligned); calls sharing one workspace must
  *     be ordered on one stream.
  *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE fp32), fp32 is IEEE float.
- *   - Strides are in ELEMENTS. head_dim must be 128 and contiguous (stride 1).
+ *   - Strides are in ELEMENTS. head_dim must be contiguous (stride 1) and 128; the attention
+ *     calls (full, retrieval, indexed, tree) and tf_kv_append also accept 64, the head size of
+ *     the small draft model whose StreamingLLM cache (sinks + recent window) the indexed call
+ *     reads. Q, O then have 64 columns; workspace queries return the (larger) 128 figure.
  *   - Every call returns a status: TF_OK, or a negative TF_ERR_* after which nothing was
  *     enqueued. Errors are detected on the host before launch; the library never aborts.
  *   - Shapes are fixed per call and no call reads device memory on the host, so a sequence
@@ -48,7 +51,7 @@ extern "C" {
 
 #define TF_OK 0
 #define TF_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, inconsistent shapes      */
-#define TF_ERR_UNSUPPORTED (-2) /* head_dim != 128, G > 8, k_chunks > 2048, ...              */
+#define TF_ERR_UNSUPPORTED (-2) /* head_dim not supported, G > 8, k_chunks > 2048, ...        */
 #define TF_ERR_WORKSPACE (-3)   /* workspace missing, misaligned or too small                */
 #define TF_ERR_HIP (-4)         /* a HIP runtime call (kernel launch) reported an error      */
 
@@ -65,7 +68,7 @@ extern "C" {
 typedef struct tf_kv_desc {
     int32_t batch;
     int32_t heads;    /* MHA: query heads = KV heads */
-    int32_t head_dim; /* must be TF_HEAD_DIM */
+    int32_t head_dim; /* TF_HEAD_DIM, or 64 for the attention calls and tf_kv_append */
     int32_t reserved; /* set to 0 */
     int64_t capacity; /* allocated tokens per (b,h) */
     int64_t stride_b, stride_h, stride_t;

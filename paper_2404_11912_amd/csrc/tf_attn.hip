@@ -59,8 +59,12 @@ struct AttnParams {
 
 __device__ __forceinline__ float safe_max(float m) { return m == -INFINITY ? 0.0f : m; }
 
-template <bool kIndexed, int kDepth>
+// kD = head dim (128, or 64 for the small draft model's cache): kD/32 K loads and bf16 MFMAs per
+// tile, kD/16 output dims (accumulators) per lane.
+template <bool kIndexed, int kDepth, int kD>
 __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
+    constexpr int kNK = kD / 32;
+    constexpr int kNE = kD / 16;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
@@ -92,19 +96,28 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     const char *Vb = reinterpret_cast<const char *>(p.V + (int64_t)b * p.sb + (int64_t)h * p.sh);
     const int64_t row_bytes = p.st * 2;
     const uint32_t k_off = (uint32_t)(r * row_bytes + s * 16);  // K: token r, dims 8s.. (+64 B per kk)
-    uint32_t v_off[4];                                          // V: token 4s+i, dims 8r..
+    uint32_t v_off[4];                                          // V: token 4s+i, dims kNE*r..
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v_off[i] = (uint32_t)((4 * s + i) * row_bytes + r * 16);
+    for (int i = 0; i < 4; ++i) v_off[i] = (uint32_t)((4 * s + i) * row_bytes + r * (kNE * 2));
+    // one lane's share of a V row: 16 bytes (head dim 128) or 8 bytes (64, upper half unused)
+    auto ldv = [](const void *ptr) -> uint4 {
+        if constexpr (kD == 128) {
+            return ld16_stream(ptr);
+        } else {
+            const uint2 h = ld8_stream(ptr);
+            return make_uint4(h.x, h.y, 0u, 0u);
+        }
+    };
 
     // Q operand of the QK^T MFMAs, kept in LDS (re-read per tile: 4 KiB per tile is nothing for
     // LDS, and 16 VGPRs fewer per lane buy a third wave per SIMD): entry [kk][lane] holds
     // Q[query r][32kk + 8s .. +8] for lane (r,s), zero for r >= G
-    __shared__ uint4 sm_q[4][kWave];
+    __shared__ uint4 sm_q[kNK][kWave];
     if (wave == 0) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < kNK; ++kk) {
             uint4 qv = make_uint4(0, 0, 0, 0);
-            if (r < p.G) qv = ld16(p.Q + ((int64_t)bh * p.G + r) * kHeadDim + kk * 32 + s * 8);
+            if (r < p.G) qv = ld16(p.Q + ((int64_t)bh * p.G + r) * kD + kk * 32 + s * 8);
             sm_q[kk][lane] = qv;
         }
     }
@@ -115,9 +128,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     const int n_all = p.masked ? len - p.G : len;
     const uint32_t my_mask = (uint32_t)(p.tail_mask >> (8 * (r & 7))) & 0xffu;  // this lane's query
 
-    f32x4_t o[8];
+    f32x4_t o[kNE];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < kNE; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
     // indexed mode: cache row of virtual token v, or -1 if it does not exist
@@ -137,17 +150,17 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     // A tile that is not `live` (software-pipeline slots past the wave's last tile) is loaded
     // from one fixed valid location with all lanes on the same 16 bytes, so the number of loads
     // in flight never depends on control flow and the dummy costs one 64-byte request.
-    auto load_k = [&](int t0, bool live, uint4(&k)[4], int &rows) {
+    auto load_k = [&](int t0, bool live, uint4(&k)[kNK], int &rows) {
         if constexpr (kIndexed) {
             rows = live ? virtual_row(t0 + r) : -1;
             const char *kp = Kb + (int64_t)max(rows, 0) * row_bytes + s * 16;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16_stream(kp + kk * 64);
+            for (int kk = 0; kk < kNK; ++kk) k[kk] = ld16_stream(kp + kk * 64);
         } else {
             const char *base = Kb + (int64_t)(live ? t0 : t_begin) * row_bytes;
             const uint32_t off = live ? k_off : 0u;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) k[kk] = ld16_stream(base + off + kk * 64);
+            for (int kk = 0; kk < kNK; ++kk) k[kk] = ld16_stream(base + off + kk * 64);
         }
     };
     // returns (indexed mode) the 4-bit validity mask of this lane's tokens 4s+i
@@ -159,25 +172,25 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
             for (int i = 0; i < 4; ++i) {
                 const int rv = __shfl(rows, 4 * s + i, kWave);   // row of token 4s+i (held by lane r'=4s+i)
                 vm |= (rv >= 0) << i;
-                v[i] = ld16_stream(Vb + (int64_t)max(rv, 0) * row_bytes + r * 16);
+                v[i] = ldv(Vb + (int64_t)max(rv, 0) * row_bytes + r * (kNE * 2));
             }
         } else {
             const char *base = Vb + (int64_t)(live ? t0 : t_begin) * row_bytes;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = ld16_stream(base + (live ? v_off[i] : 0u));
+            for (int i = 0; i < 4; ++i) v[i] = ldv(base + (live ? v_off[i] : 0u));
         }
         return vm;
     };
 
     // S^T tile: four bf16 MFMAs over the head dim, then the log2-domain scale
-    auto qk_tile = [&](const uint4(&k)[4], float(&z)[4]) {
+    auto qk_tile = [&](const uint4(&k)[kNK], float(&z)[4]) {
         f32x4_t sc = f32x4_t{0.f, 0.f, 0.f, 0.f};
         asm volatile("" ::: "memory");  // keep the Q reads inside the loop (not hoisted into registers)
-        uint4 qb[4];
+        uint4 qb[kNK];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) qb[kk] = sm_q[kk][lane];
+        for (int kk = 0; kk < kNK; ++kk) qb[kk] = sm_q[kk][lane];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
+        for (int kk = 0; kk < kNK; ++kk)
             sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k[kk]),
                                                          __builtin_bit_cast(bf16x8_t, qb[kk]), sc, 0, 0, 0);
 #pragma unroll
@@ -205,7 +218,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
             for (int j = 0; j < 4; ++j) {
                 const float aj = __shfl(alpha, 4 * s + j, kWave);  // factor of query 4s+j
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e][j] *= aj;
+                for (int e = 0; e < kNE; ++e) o[e][j] *= aj;
             }
             m_run = m_new;
         }
@@ -218,7 +231,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         for (int i = 0; i < 4; ++i) {
             const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < kNE; ++e) {
                 const float vf = (e & 1) ? bf16hi(w[e >> 1]) : bf16lo(w[e >> 1]);
                 o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[i], vf, o[e], 0, 0, 0);
             }
@@ -235,7 +248,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     const int n_mine_tiles = (n_full - wave + kWaves - 1) / kWaves;
     if (n_mine_tiles > 0) {
         constexpr int step = kWaves * kTile;
-        uint4 kb[kDepth][4], vb[kDepth][4];
+        uint4 kb[kDepth][kNK], vb[kDepth][4];
         int rws[kDepth], vms[kDepth];
         float z[4];
         const int t_first = t_begin + wave * kTile;
@@ -261,14 +274,14 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     // last valid token and masked; handled by the wave whose turn it would be
     if (!kIndexed && t_begin + n_full * kTile < t_end && (n_full % kWaves) == wave) {
         const int t0 = t_begin + n_full * kTile;
-        uint4 kt[4], vt[4];
+        uint4 kt[kNK], vt[4];
         float z[4];
         const char *kp = Kb + (int64_t)min(t0 + r, last_row) * row_bytes + s * 16;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) kt[kk] = ld16_stream(kp + kk * 64);
+        for (int kk = 0; kk < kNK; ++kk) kt[kk] = ld16_stream(kp + kk * 64);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            vt[i] = ld16_stream(Vb + (int64_t)min(t0 + 4 * s + i, last_row) * row_bytes + r * 16);
+            vt[i] = ldv(Vb + (int64_t)min(t0 + 4 * s + i, last_row) * row_bytes + r * (kNE * 2));
         qk_tile(kt, z);
         softmax_pv(t0, z, vt, 0xf);
     }
@@ -277,7 +290,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     l_run += __shfl_xor(l_run, 16, kWave);
     l_run += __shfl_xor(l_run, 32, kWave);
 
-    __shared__ float sm_o[kWaves][kGPad][kHeadDim];
+    __shared__ float sm_o[kWaves][kGPad][kD];
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
     if (s == 0) {
@@ -287,18 +300,17 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     if (s < 2) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            float4 lo = make_float4(o[0][j], o[1][j], o[2][j], o[3][j]);
-            float4 hi = make_float4(o[4][j], o[5][j], o[6][j], o[7][j]);
-            float *dst = &sm_o[wave][4 * s + j][8 * r];
-            *reinterpret_cast<float4 *>(dst) = lo;
-            *reinterpret_cast<float4 *>(dst + 4) = hi;
+            float *dst = &sm_o[wave][4 * s + j][kNE * r];
+            *reinterpret_cast<float4 *>(dst) = make_float4(o[0][j], o[1][j], o[2][j], o[3][j]);
+            if constexpr (kNE == 8)
+                *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4][j], o[5][j], o[6][j], o[7][j]);
         }
     }
     __syncthreads();
 
     const int64_t pbase = (int64_t)bh * p.nsplit + split;
-    for (int idx = tid; idx < p.G * kHeadDim; idx += 256) {
-        const int g = idx >> 7, dim = idx & 127;
+    for (int idx = tid; idx < p.G * kD; idx += 256) {
+        const int g = idx / kD, dim = idx % kD;
         float mw[kWaves], M = -INFINITY;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
@@ -313,7 +325,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
             acc += a * sm_o[w][g][dim];
             lsum += a * sm_l[w][g];
         }
-        p.part_o[(pbase * kGPad + g) * kHeadDim + dim] = acc;
+        p.part_o[(pbase * kGPad + g) * kD + dim] = acc;
         if (dim == 0) {
             p.part_ml[(pbase * 2 + 0) * kGPad + g] = M;
             p.part_ml[(pbase * 2 + 1) * kGPad + g] = lsum;
@@ -325,9 +337,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
 // per-split maxima and sums are staged in LDS, turned into weights once, and each group
 // accumulates every 4th split with independent loads in flight; groups are summed in LDS.
 constexpr int kCombineThreads = 512;
-constexpr int kCombineGroups = kCombineThreads / kHeadDim;
 constexpr int kMaxSplits = 2048;
 
+template <int kD>
 __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const float *__restrict__ part_o,
                                                                        const float *__restrict__ part_ml,
                                                                        int nsplit, int G, float *__restrict__ O,
@@ -335,7 +347,8 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const flo
     __shared__ float sm_w[kMaxSplits];   // running max, then weight exp2(m - M), per split
     __shared__ float sm_l[kMaxSplits];
     __shared__ float sm_red[kCombineThreads / 64];
-    __shared__ float sm_acc[kCombineGroups][kHeadDim];
+    constexpr int kCombineGroups = kCombineThreads / kD;
+    __shared__ float sm_acc[kCombineGroups][kD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bh = blockIdx.x / G, g = blockIdx.x - bh * G;
     const int64_t base = (int64_t)bh * nsplit;
@@ -370,9 +383,9 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const flo
 #pragma unroll
     for (int w = 0; w < kCombineThreads / 64; ++w) L += sm_red[w];
 
-    const int dim = tid & (kHeadDim - 1), grp = tid >> 7;
-    const float *po = part_o + (base * kGPad + g) * kHeadDim + dim;
-    constexpr int64_t split_stride = (int64_t)kGPad * kHeadDim;
+    const int dim = tid % kD, grp = tid / kD;
+    const float *po = part_o + (base * kGPad + g) * kD + dim;
+    constexpr int64_t split_stride = (int64_t)kGPad * kD;
     float acc = 0.f;
     int sp = grp;
     for (; sp + 3 * kCombineGroups < nsplit; sp += 4 * kCombineGroups) {
@@ -388,12 +401,12 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const flo
     for (; sp < nsplit; sp += kCombineGroups) acc += sm_w[sp] * po[(int64_t)sp * split_stride];
     sm_acc[grp][dim] = acc;
     __syncthreads();
-    if (tid < kHeadDim) {
+    if (tid < kD) {
         float tot = sm_acc[0][tid];
 #pragma unroll
         for (int q = 1; q < kCombineGroups; ++q) tot += sm_acc[q][tid];
         const int64_t row = (int64_t)bh * G + g;
-        O[row * kHeadDim + tid] = L > 0.f ? tot / L : 0.f;
+        O[row * kD + tid] = L > 0.f ? tot / L : 0.f;
         if (LSE && tid == 0) LSE[row] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
     }
 }
@@ -484,6 +497,7 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
     return SplitPlan{(int)ns, (int)tps};
 }
 
+// sized for head dim 128 whatever the call's head dim (the queries do not take it)
 static size_t attn_ws_bytes(int64_t BH, const SplitPlan &sp) {
     return (size_t)BH * sp.nsplit * (kGPad * kHeadDim + 2 * kGPad) * sizeof(float);
 }
@@ -512,7 +526,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
                 int64_t kv_len_all, int32_t G, float scale, int32_t causal, float *O, float *LSE, void *ws,
                 size_t ws_bytes, void *stream, bool retrieval, const IndexedArgs *ix, const uint8_t *tail_mask) {
     if (!Q || !K || !V || !O) return TF_ERR_INVALID_ARG;
-    int rc = check_desc(kd);
+    int rc = check_desc(kd, true);
     if (rc != TF_OK) return rc;
     if (G < 1) return TF_ERR_INVALID_ARG;
     if (G > TF_MAX_QUERIES) return TF_ERR_UNSUPPORTED;
@@ -557,7 +571,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.tokens_per_split = sp.tokens_per_split;
     p.scale_log2 = scale * kLog2e;
     p.part_o = static_cast<float *>(ws);
-    p.part_ml = p.part_o + (size_t)BH * sp.nsplit * kGPad * kHeadDim;
+    p.part_ml = p.part_o + (size_t)BH * sp.nsplit * kGPad * kd->head_dim;
     p.idx = ix ? ix->idx : nullptr;
     p.k_chunks = ix ? ix->k_chunks : 0;
     p.chunk = ix ? ix->chunk : 1;
@@ -567,12 +581,22 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(BH * sp.nsplit));
-    if (ix)
-        hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth>), grid, dim3(256), 0, st, p);
-    else
-        hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth>), grid, dim3(256), 0, st, p);
-    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(BH * G)), dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
-                       sp.nsplit, G, O, LSE);
+    const dim3 cgrid((unsigned)(BH * G));
+    if (kd->head_dim == 128) {
+        if (ix)
+            hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth, 128>), grid, dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth, 128>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_combine_kernel<128>), cgrid, dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
+                           sp.nsplit, G, O, LSE);
+    } else {
+        if (ix)
+            hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth, 64>), grid, dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth, 64>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_combine_kernel<64>), cgrid, dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
+                           sp.nsplit, G, O, LSE);
+    }
     return hip_status(hipGetLastError());
 }
 

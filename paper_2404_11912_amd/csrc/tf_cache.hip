@@ -1,6 +1,7 @@
 // tf_kv_append: write the K/V rows of newly decoded tokens into a cache (Sec. 4.3: "we overwrite
 // tokens with the least importance" for the retrieval cache; plain append for the full cache).
-// A strided row copy: one wave moves 4 rows (256 B each) of K and of V with 16-byte accesses.
+// A strided row copy: one wave moves 4 rows of K and of V with 16-byte accesses (16 lanes per row;
+// rows of head_dim 64 use the first 8 of them).
 #include "tf_common.hpp"
 
 namespace tf {
@@ -10,7 +11,7 @@ struct AppendParams {
     uint16_t *K, *V;
     int64_t sb, sh, st, capacity;
     const int32_t *pos;
-    int32_t pos_all, H, n, row_blocks;
+    int32_t pos_all, H, n, row_blocks, head_dim;
 };
 
 __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams p) {
@@ -21,7 +22,8 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams p) {
     const int b = (int)(bh / p.H), h = (int)(bh - (int64_t)b * p.H);
     const int64_t dst_row = (int64_t)(p.pos ? p.pos[b] : p.pos_all) + i;
     if (dst_row < 0 || dst_row >= p.capacity) return;  // rows outside the cache are dropped
-    const int64_t src = (bh * p.n + i) * kHeadDim + (lane & 15) * 8;
+    if ((lane & 15) * 8 >= p.head_dim) return;
+    const int64_t src = (bh * p.n + i) * p.head_dim + (lane & 15) * 8;
     const int64_t dst = (int64_t)b * p.sb + (int64_t)h * p.sh + dst_row * p.st + (lane & 15) * 8;
     st16(p.K + dst, ld16(p.Kn + src));
     st16(p.V + dst, ld16(p.Vn + src));
@@ -30,7 +32,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams p) {
 int kv_append_launch(const void *Knew, const void *Vnew, int32_t n, void *K, void *V, const tf_kv_desc *kd,
                      const int32_t *pos, int64_t pos_all, void *stream) {
     if (!Knew || !Vnew || !K || !V) return TF_ERR_INVALID_ARG;
-    int rc = check_desc(kd);
+    int rc = check_desc(kd, true);
     if (rc != TF_OK) return rc;
     if (n < 0 || pos_all < 0) return TF_ERR_INVALID_ARG;
     if (!pos && pos_all + n > kd->capacity) return TF_ERR_INVALID_ARG;
@@ -51,6 +53,7 @@ int kv_append_launch(const void *Knew, const void *Vnew, int32_t n, void *K, voi
     p.pos_all = (int32_t)pos_all;
     p.H = kd->heads;
     p.n = n;
+    p.head_dim = kd->head_dim;
     p.row_blocks = (n + 15) / 16;
     if (BH * p.row_blocks >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)(BH * p.row_blocks)), dim3(256), 0,

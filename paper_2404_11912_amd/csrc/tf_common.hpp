@@ -32,6 +32,11 @@ __device__ __forceinline__ uint4 ld16_stream(const void *p) {
     const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ uint2 ld8_stream(const void *p) {
+    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+    const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(p));
+    return make_uint2(v.x, v.y);
+}
 __device__ __forceinline__ float4 ldf4_stream(const float *p) {
     const f32x4v_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4v_t *>(p));
     return make_float4(v.x, v.y, v.z, v.w);
@@ -53,12 +58,14 @@ inline int hip_status(hipError_t e) { return e == hipSuccess ? TF_OK : TF_ERR_HI
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-// validates the parts of a descriptor every call relies on
-inline int check_desc(const tf_kv_desc *d) {
+// validates the parts of a descriptor every call relies on. The retrieval calls (summaries,
+// scoring, gather) exist for head_dim 128 only; the attention calls and the cache append also
+// take head_dim 64 (`allow_64`), the shape of the small draft model's cache.
+inline int check_desc(const tf_kv_desc *d, bool allow_64 = false) {
     if (!d) return TF_ERR_INVALID_ARG;
     if (d->batch <= 0 || d->heads <= 0 || d->capacity <= 0) return TF_ERR_INVALID_ARG;
-    if (d->head_dim != kHeadDim) return TF_ERR_UNSUPPORTED;
-    if (d->stride_t < kHeadDim || d->stride_b < 0 || d->stride_h < 0) return TF_ERR_INVALID_ARG;
+    if (d->head_dim != kHeadDim && !(allow_64 && d->head_dim == 64)) return TF_ERR_UNSUPPORTED;
+    if (d->stride_t < d->head_dim || d->stride_b < 0 || d->stride_h < 0) return TF_ERR_INVALID_ARG;
     if ((d->stride_t % 8) || (d->stride_h % 8) || (d->stride_b % 8)) return TF_ERR_INVALID_ARG;
     return TF_OK;
 }

@@ -85,7 +85,8 @@ def test_options(lib):
 def test_host_side_argument_checks(lib):
     """Every call validates on the host and returns before touching the GPU."""
     d = tf_kv_desc(1, 2, 128, 0, 64, 2 * 64 * 128, 64 * 128, 128)
-    bad_dim = tf_kv_desc(1, 2, 64, 0, 64, 2 * 64 * 64, 64 * 64, 64)
+    bad_dim = tf_kv_desc(1, 2, 96, 0, 64, 2 * 64 * 96, 64 * 96, 96)
+    d64 = tf_kv_desc(1, 2, 64, 0, 64, 2 * 64 * 64, 64 * 64, 64)        # attention and append only
     p = ctypes.c_void_p(4096)          # never dereferenced on the host
     ref = ctypes.byref
     # null pointers
@@ -99,6 +100,8 @@ def test_host_side_argument_checks(lib):
     # unsupported shapes
     assert lib.tf_decode_attn_full(p, p, p, ref(bad_dim), None, 64, 4, 1.0, 1, p, None, p, 1 << 20, None) == -2
     assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 64, 9, 1.0, 1, p, None, p, 1 << 20, None) == -2
+    assert lib.tf_chunk_summarize(p, ref(d64), 8, 0, 8, p, 8, None) == -2
+    assert lib.tf_decode_attn_full(p, p, p, ref(d64), None, 64, 4, 1.0, 1, p, None, p, 16, None) == -3   # accepted up to the workspace check
     assert lib.tf_chunk_topk_gather(p, p, 8, p, p, ref(d), 8, None, 8, 4096, p, None, None, None, None,
                                     p, 1 << 20, None) == -2
     # inconsistent sizes
