@@ -64,12 +64,16 @@ extern "C" {
  * Element (b,h,t,j) lives at base + b*stride_b + h*stride_h + t*stride_t + j.
  * The native layout [B,H,capacity,128] has stride_t = 128, stride_h = capacity*128,
  * stride_b = heads*capacity*128. Base pointer and all strides must keep rows 16-byte
- * aligned (strides multiples of 8 elements). K and V of one call share one descriptor. */
+ * aligned (strides multiples of 8 elements). K and V of one call share one descriptor.
+ * Grouped-query attention: with q_group > 1 the attention calls take Q, O of
+ * [batch, heads*q_group, G, head_dim] and LSE of [batch, heads*q_group, G]; query head q uses KV
+ * head q / q_group. G * q_group <= 16 (the group's query rows share one pass over its K/V);
+ * workspace queries then take G * q_group as their G. Other calls ignore q_group. */
 typedef struct tf_kv_desc {
     int32_t batch;
-    int32_t heads;    /* MHA: query heads = KV heads */
+    int32_t heads;    /* KV heads */
     int32_t head_dim; /* TF_HEAD_DIM, or 64 for the attention calls and tf_kv_append */
-    int32_t reserved; /* set to 0 */
+    int32_t q_group;  /* query heads per KV head for the attention calls; 0 or 1 = MHA */
     int64_t capacity; /* allocated tokens per (b,h) */
     int64_t stride_b, stride_h, stride_t;
 } tf_kv_desc;

@@ -6,6 +6,7 @@ this package. It never imports the HIP package and shares no code with it.
 from .tf_oracle import (  # noqa: F401
     accept,
     attention,
+    attention_gqa,
     attention_indexed,
     attention_tree,
     build_oracle,

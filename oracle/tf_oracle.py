@@ -180,6 +180,19 @@ def attention_indexed(Q, K, V, idx, c: int, kv_len=None, recent_begin=None, scal
     return O, LSE
 
 
+def attention_gqa(Q, K, V, kv_len=None, scale: float = 1.0, causal: bool = True):
+    """Grouped-query attention written as its definition: query head q attends with the K/V of KV
+    head q // q_group (q_group = query heads / KV heads); each KV head is repeated for its group
+    and the plain attention is called. Q [B,Hq,G,d], K,V [B,Hkv,N,d] -> (O, LSE) float64."""
+    Q, K, V = _u16(Q), _u16(K), _u16(V)
+    q_group = Q.shape[1] // K.shape[1]
+    assert q_group * K.shape[1] == Q.shape[1]
+    Kr = np.ascontiguousarray(np.repeat(K, q_group, axis=1))
+    Vr = np.ascontiguousarray(np.repeat(V, q_group, axis=1))
+    O, LSE, _ = attention(Q, Kr, Vr, kv_len=kv_len, scale=scale, causal=causal)
+    return O, LSE
+
+
 def attention_tree(Q, K, V, tail_mask, kv_len=None, scale: float = 1.0):
     """Verification attention for a speculated token tree (Sec. 5.3.3), written as its definition:
     the G speculated tokens are the last G rows of each sequence; query g attends to the context

@@ -39,7 +39,7 @@ class TfError(RuntimeError):
 
 class tf_kv_desc(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("capacity", ctypes.c_int64),
+                ("q_group", ctypes.c_int32), ("capacity", ctypes.c_int64),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_t", ctypes.c_int64)]
 
 
@@ -201,11 +201,12 @@ def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream, 
     kv_desc(V)
     if V.stride() != K.stride() or V.shape != K.shape:
         raise ValueError("K and V must share shape and strides")
-    if Q.dim() != 4 or Q.shape[0] != d.batch or Q.shape[1] != d.heads or Q.shape[3] != d.head_dim:
-        raise ValueError("Q must be [B,H,G,d]")
+    if Q.dim() != 4 or Q.shape[0] != d.batch or Q.shape[1] % d.heads or Q.shape[3] != d.head_dim:
+        raise ValueError("Q must be [B,H*q_group,G,d]")
+    d.q_group = Q.shape[1] // d.heads                     # grouped-query heads share their KV head's pass
     G = Q.shape[2]
     if tuple(O.shape) != tuple(Q.shape):
-        raise ValueError("O must be [B,H,G,d]")
+        raise ValueError("O must be [B,H*q_group,G,d]")
     if LSE is not None:
         _need(LSE, torch.float32, "LSE")
         if tuple(LSE.shape) != tuple(Q.shape[:3]):
@@ -216,7 +217,7 @@ def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream, 
         kv_len_all = K.shape[2]
     if ws is None:
         ws_name = "tf_decode_attn_full" if tail_mask is not None else name
-        nbytes = getattr(lib, ws_name + "_workspace_bytes")(d.batch, d.heads, int(kv_len_all), int(G))
+        nbytes = getattr(lib, ws_name + "_workspace_bytes")(d.batch, d.heads, int(kv_len_all), int(G) * d.q_group)
         ws = workspace(nbytes, K.device)
     if tail_mask is not None:
         rows = [int(m) for m in tail_mask]
@@ -278,8 +279,9 @@ def tf_decode_attn_indexed(Q, K, V, idx, chunk: int, O, LSE=None, kv_len=None, k
     kv_desc(V)
     if V.stride() != K.stride() or V.shape != K.shape:
         raise ValueError("K and V must share shape and strides")
-    if Q.dim() != 4 or Q.shape[0] != d.batch or Q.shape[1] != d.heads or Q.shape[3] != d.head_dim:
-        raise ValueError("Q must be [B,H,G,d]")
+    if Q.dim() != 4 or Q.shape[0] != d.batch or Q.shape[1] % d.heads or Q.shape[3] != d.head_dim:
+        raise ValueError("Q must be [B,H*q_group,G,d]")
+    d.q_group = Q.shape[1] // d.heads
     if idx.dim() != 3 or idx.shape[0] != d.batch or idx.shape[1] != d.heads:
         raise ValueError("idx must be [B,H,k]")
     G, k = Q.shape[2], idx.shape[2]
@@ -297,7 +299,7 @@ def tf_decode_attn_indexed(Q, K, V, idx, chunk: int, O, LSE=None, kv_len=None, k
         recent_begin_all = kv_len_all
     if ws is None:
         nbytes = lib.tf_decode_attn_indexed_workspace_bytes(d.batch, d.heads, int(k), int(chunk),
-                                                            int(kv_len_all - recent_begin_all), int(G))
+                                                            int(kv_len_all - recent_begin_all), int(G) * d.q_group)
         ws = workspace(nbytes, K.device)
     _check("tf_decode_attn_indexed",
            lib.tf_decode_attn_indexed(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(idx), int(k), int(chunk),

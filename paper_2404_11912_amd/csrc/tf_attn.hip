@@ -20,13 +20,14 @@
 //     anything in L2 / the last-level cache (+15% bandwidth measured).
 // The 4 waves merge (m, l, O) through LDS and write one fp32 partial per split; a small
 // second kernel merges the splits by log-sum-exp and normalises.
+#include <type_traits>
+
 #include "tf_common.hpp"
 
 namespace tf {
 
 constexpr int kTile = 16;    // tokens per MFMA tile
 constexpr int kWaves = 4;    // waves per workgroup
-constexpr int kGPad = 8;     // query rows kept in the partials
 // tiles in flight per wave. Measured at 128K context, one workgroup per CU: depth 2 305 us,
 // depth 3 307 us, depth 4 307 us per layer -- the stream is not latency-bound, so the
 // shallowest pipeline (fewest registers) is used.
@@ -37,7 +38,10 @@ struct AttnParams {
     int64_t sb, sh, st;
     const int32_t *kv_len;
     int32_t kv_len_all;  // plain: upper bound of the cache length; indexed: of the virtual length
-    int32_t H, G;
+    // G: query rows per KV head = (speculated tokens) x (query heads per KV head), <= 16: they are
+    // the columns of the QK^T MFMA, so grouped-query heads ride along for free. Row r is token
+    // r % Gm of query head r / Gm of the group; Gm = speculated tokens.
+    int32_t H, G, Gm;
     // masked != 0: the last G tokens of the sequence are the queries' own; query g sees the
     // tokens before them and the j-th of them iff bit j of byte g of tail_mask is set (causal:
     // bits 0..g; a token tree: the node's ancestors and itself). masked == 0: every query sees all.
@@ -45,8 +49,8 @@ struct AttnParams {
     uint64_t tail_mask;
     int32_t nsplit, tokens_per_split;
     float scale_log2;
-    float *part_o;   // [BH][nsplit][kGPad][128]
-    float *part_ml;  // [BH][nsplit][2][kGPad]   (running max in log2 units, then sum)
+    float *part_o;   // [BH][nsplit][rows][head dim], rows = 8 or 16 (the kernel's kRows)
+    float *part_ml;  // [BH][nsplit][2][rows]   (running max in log2 units, then sum)
     // indexed mode only: the virtual sequence of (b,h) is the chunks idx[b,h,0..k_chunks) of the
     // cache (chunk j = rows idx*chunk .. idx*chunk+chunk-1, negative entries skipped) followed
     // by the cache rows [recent_begin, len)
@@ -61,7 +65,7 @@ __device__ __forceinline__ float safe_max(float m) { return m == -INFINITY ? 0.0
 
 // kD = head dim (128, or 64 for the small draft model's cache): kD/32 K loads and bf16 MFMAs per
 // tile, kD/16 output dims (accumulators) per lane.
-template <bool kIndexed, int kDepth, int kD>
+template <bool kIndexed, int kDepth, int kD, int kRows>
 __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     constexpr int kNK = kD / 32;
     constexpr int kNE = kD / 16;
@@ -125,8 +129,8 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
 
     // tokens < n_all are visible to every query; of the last G tokens this lane's query sees
     // those whose bit is set in my_mask
-    const int n_all = p.masked ? len - p.G : len;
-    const uint32_t my_mask = (uint32_t)(p.tail_mask >> (8 * (r & 7))) & 0xffu;  // this lane's query
+    const int n_all = p.masked ? len - p.Gm : len;
+    const uint32_t my_mask = (uint32_t)(p.tail_mask >> (8 * (r % p.Gm))) & 0xffu;  // this lane's query
 
     f32x4_t o[kNE];
 #pragma unroll
@@ -290,14 +294,14 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     l_run += __shfl_xor(l_run, 16, kWave);
     l_run += __shfl_xor(l_run, 32, kWave);
 
-    __shared__ float sm_o[kWaves][kGPad][kD];
+    __shared__ float sm_o[kWaves][kRows][kD];
     __shared__ float sm_m[kWaves][16];
     __shared__ float sm_l[kWaves][16];
     if (s == 0) {
         sm_m[wave][r] = m_run;
         sm_l[wave][r] = l_run;
     }
-    if (s < 2) {
+    if (4 * s < kRows) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float *dst = &sm_o[wave][4 * s + j][kNE * r];
@@ -325,10 +329,10 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
             acc += a * sm_o[w][g][dim];
             lsum += a * sm_l[w][g];
         }
-        p.part_o[(pbase * kGPad + g) * kD + dim] = acc;
+        p.part_o[(pbase * kRows + g) * kD + dim] = acc;
         if (dim == 0) {
-            p.part_ml[(pbase * 2 + 0) * kGPad + g] = M;
-            p.part_ml[(pbase * 2 + 1) * kGPad + g] = lsum;
+            p.part_ml[(pbase * 2 + 0) * kRows + g] = M;
+            p.part_ml[(pbase * 2 + 1) * kRows + g] = lsum;
         }
     }
 }
@@ -342,7 +346,8 @@ constexpr int kMaxSplits = 2048;
 template <int kD>
 __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const float *__restrict__ part_o,
                                                                        const float *__restrict__ part_ml,
-                                                                       int nsplit, int G, float *__restrict__ O,
+                                                                       int nsplit, int G, int rows,
+                                                                       float *__restrict__ O,
                                                                        float *__restrict__ LSE) {
     __shared__ float sm_w[kMaxSplits];   // running max, then weight exp2(m - M), per split
     __shared__ float sm_l[kMaxSplits];
@@ -355,9 +360,9 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const flo
 
     float mx = -INFINITY;
     for (int sp = tid; sp < nsplit; sp += kCombineThreads) {
-        const float m = part_ml[((base + sp) * 2 + 0) * kGPad + g];
+        const float m = part_ml[((base + sp) * 2 + 0) * rows + g];
         sm_w[sp] = m;
-        sm_l[sp] = part_ml[((base + sp) * 2 + 1) * kGPad + g];
+        sm_l[sp] = part_ml[((base + sp) * 2 + 1) * rows + g];
         mx = fmaxf(mx, m);
     }
 #pragma unroll
@@ -384,8 +389,8 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const flo
     for (int w = 0; w < kCombineThreads / 64; ++w) L += sm_red[w];
 
     const int dim = tid % kD, grp = tid / kD;
-    const float *po = part_o + (base * kGPad + g) * kD + dim;
-    constexpr int64_t split_stride = (int64_t)kGPad * kD;
+    const float *po = part_o + (base * rows + g) * kD + dim;
+    const int64_t split_stride = (int64_t)rows * kD;
     float acc = 0.f;
     int sp = grp;
     for (; sp + 3 * kCombineGroups < nsplit; sp += 4 * kCombineGroups) {
@@ -497,15 +502,17 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
     return SplitPlan{(int)ns, (int)tps};
 }
 
-// sized for head dim 128 whatever the call's head dim (the queries do not take it)
-static size_t attn_ws_bytes(int64_t BH, const SplitPlan &sp) {
-    return (size_t)BH * sp.nsplit * (kGPad * kHeadDim + 2 * kGPad) * sizeof(float);
+// sized for head dim 128 whatever the call's head dim (the queries do not take it); 8 query rows per
+// KV head, 16 when there are more than 8
+static int rows_of(int G) { return G > 8 ? 16 : 8; }
+static size_t attn_ws_bytes(int64_t BH, const SplitPlan &sp, int G) {
+    return (size_t)BH * sp.nsplit * (rows_of(G) * kHeadDim + 2 * rows_of(G)) * sizeof(float);
 }
 
 size_t attn_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G, bool retrieval) {
     if (batch <= 0 || heads <= 0 || kv_len_all <= 0 || G <= 0) return 0;
     const int64_t BH = (int64_t)batch * heads;
-    return attn_ws_bytes(BH, plan_splits(BH, kv_len_all, retrieval ? kPlanRetrieval : kPlanFull));
+    return attn_ws_bytes(BH, plan_splits(BH, kv_len_all, retrieval ? kPlanRetrieval : kPlanFull), G);
 }
 
 
@@ -519,7 +526,7 @@ size_t attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chun
     const int64_t lv = (int64_t)k_chunks * chunk + recent_len_all;
     if (lv <= 0) return 0;
     const int64_t BH = (int64_t)batch * heads;
-    return attn_ws_bytes(BH, plan_splits(BH, lv, kPlanIndexed));
+    return attn_ws_bytes(BH, plan_splits(BH, lv, kPlanIndexed), G);
 }
 
 int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
@@ -528,8 +535,11 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     if (!Q || !K || !V || !O) return TF_ERR_INVALID_ARG;
     int rc = check_desc(kd, true);
     if (rc != TF_OK) return rc;
-    if (G < 1) return TF_ERR_INVALID_ARG;
+    if (G < 1 || kd->q_group < 0) return TF_ERR_INVALID_ARG;
     if (G > TF_MAX_QUERIES) return TF_ERR_UNSUPPORTED;
+    const int q_group = kd->q_group > 0 ? kd->q_group : 1;  // query heads per KV head
+    if ((int64_t)G * q_group > 16) return TF_ERR_UNSUPPORTED; // the rows are the 16 columns of one MFMA
+    const int GQ = G * q_group;
     if (kv_len_all < 1 || kv_len_all > kd->capacity) return TF_ERR_INVALID_ARG;
     if (kd->capacity > (int64_t)1 << 30 || kd->stride_t > (1 << 24)) return TF_ERR_UNSUPPORTED;
     int64_t plan_len = kv_len_all;  // length the splits are planned on
@@ -548,7 +558,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     const int64_t BH = (int64_t)kd->batch * kd->heads;
     const SplitPlan sp = plan_splits(BH, plan_len, ix ? kPlanIndexed : (retrieval ? kPlanRetrieval : kPlanFull));
     if (BH * sp.nsplit >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
-    if (!ws || !aligned(ws, 256) || ws_bytes < attn_ws_bytes(BH, sp)) return TF_ERR_WORKSPACE;
+    if (!ws || !aligned(ws, 256) || ws_bytes < attn_ws_bytes(BH, sp, GQ)) return TF_ERR_WORKSPACE;
 
     AttnParams p;
     p.Q = static_cast<const uint16_t *>(Q);
@@ -560,7 +570,8 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.kv_len = kv_len;
     p.kv_len_all = (int32_t)plan_len;
     p.H = kd->heads;
-    p.G = G;
+    p.G = GQ;
+    p.Gm = G;
     p.masked = (causal || tail_mask) ? 1 : 0;
     p.tail_mask = 0;
     for (int g = 0; g < G; ++g) {
@@ -571,7 +582,8 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.tokens_per_split = sp.tokens_per_split;
     p.scale_log2 = scale * kLog2e;
     p.part_o = static_cast<float *>(ws);
-    p.part_ml = p.part_o + (size_t)BH * sp.nsplit * kGPad * kd->head_dim;
+    const int rows = rows_of(GQ);
+    p.part_ml = p.part_o + (size_t)BH * sp.nsplit * rows * kd->head_dim;
     p.idx = ix ? ix->idx : nullptr;
     p.k_chunks = ix ? ix->k_chunks : 0;
     p.chunk = ix ? ix->chunk : 1;
@@ -581,21 +593,23 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(BH * sp.nsplit));
-    const dim3 cgrid((unsigned)(BH * G));
+    const dim3 cgrid((unsigned)(BH * GQ));
+    auto launch = [&](auto d_tag, auto rows_tag) {
+        constexpr int kD = decltype(d_tag)::value, kRows = decltype(rows_tag)::value;
+        if (ix)
+            hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth, kD, kRows>), grid, dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth, kD, kRows>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_combine_kernel<kD>), cgrid, dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
+                           sp.nsplit, GQ, kRows, O, LSE);
+    };
+    using std::integral_constant;
     if (kd->head_dim == 128) {
-        if (ix)
-            hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth, 128>), grid, dim3(256), 0, st, p);
-        else
-            hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth, 128>), grid, dim3(256), 0, st, p);
-        hipLaunchKernelGGL((attn_combine_kernel<128>), cgrid, dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
-                           sp.nsplit, G, O, LSE);
+        if (rows == 8) launch(integral_constant<int, 128>{}, integral_constant<int, 8>{});
+        else launch(integral_constant<int, 128>{}, integral_constant<int, 16>{});
     } else {
-        if (ix)
-            hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth, 64>), grid, dim3(256), 0, st, p);
-        else
-            hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth, 64>), grid, dim3(256), 0, st, p);
-        hipLaunchKernelGGL((attn_combine_kernel<64>), cgrid, dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
-                           sp.nsplit, G, O, LSE);
+        if (rows == 8) launch(integral_constant<int, 64>{}, integral_constant<int, 8>{});
+        else launch(integral_constant<int, 64>{}, integral_constant<int, 16>{});
     }
     return hip_status(hipGetLastError());
 }

@@ -173,3 +173,28 @@ def test_bad_arguments_raise():
         oracle.attention(Q, K, K, kv_len=[2], causal=True)   # fewer tokens than queries
     with pytest.raises(ValueError):
         oracle.attention(Q, K, K, kv_len=[9], causal=False)  # beyond capacity
+
+
+def test_grouped_query_oracle_reduces_to_per_head_attention():
+    """Grouped-query attention: query head q uses KV head q // q_group. Pinned head by head against
+    the plain attention on the sliced arrays, and for q_group = 1 against the plain call itself."""
+    rng = np.random.default_rng(77)
+    B, Hkv, qg, G, N = 2, 3, 4, 3, 50
+    Q = _rand_u16(rng, (B, Hkv * qg, G, D), 0.3)
+    K = _rand_u16(rng, (B, Hkv, N, D))
+    V = _rand_u16(rng, (B, Hkv, N, D))
+    kv = np.array([50, 17], dtype=np.int32)
+    O, L = oracle.attention_gqa(Q, K, V, kv_len=kv, scale=0.8, causal=True)
+    for q in range(Hkv * qg):
+        h = q // qg
+        o, l, _ = oracle.attention(np.ascontiguousarray(Q[:, q:q + 1]), np.ascontiguousarray(K[:, h:h + 1]),
+                                   np.ascontiguousarray(V[:, h:h + 1]), kv_len=kv, scale=0.8, causal=True)
+        assert np.array_equal(O[:, q:q + 1], o) and np.array_equal(L[:, q:q + 1], l)
+    # a wrong grouping (q % Hkv instead of q // q_group) would differ
+    o_wrong, _, _ = oracle.attention(np.ascontiguousarray(Q[:, 1:2]), np.ascontiguousarray(K[:, 1:2]),
+                                     np.ascontiguousarray(V[:, 1:2]), kv_len=kv, scale=0.8, causal=True)
+    assert np.max(np.abs(O[:, 1:2] - o_wrong)) > 1e-6
+    Q1 = np.ascontiguousarray(Q[:, :Hkv])
+    O1, L1 = oracle.attention_gqa(Q1, K, V, kv_len=kv, scale=0.8, causal=False)
+    O2, L2, _ = oracle.attention(Q1, K, V, kv_len=kv, scale=0.8, causal=False)
+    assert np.array_equal(O1, O2) and np.array_equal(L1, L2)
