@@ -289,6 +289,20 @@ def main():
     ev = [_timed(lambda: [step.draft_attn_indexed(l) for l in range(L)]) for _ in range(3)]
     torch.cuda.synchronize()
     indexed_us = float(np.mean([a.elapsed_time(b) for a, b in ev])) * 1e3
+    # ... the retrieval rebuild over a bf16 average-key table (half the scoring traffic)
+    Kmean_bf = torch.empty(step.Kmean.shape, dtype=torch.bfloat16, device=dev)
+    step.tf.tf_chunk_summarize_bf16(step.K, w.c, Kmean_bf, 0, w.M)
+
+    def rebuild_bf16():
+        step.tf.tf_chunk_topk_gather_bf16(step.q_r, Kmean_bf, step.K, step.V, w.c, w.k, step.idx, step.Kr, step.Vr,
+                                          ws=step.ws)
+    rebuild_bf16()
+    torch.cuda.synchronize()
+    ev = [_timed(rebuild_bf16) for _ in range(3)]
+    torch.cuda.synchronize()
+    rebuild_bf16_us = float(np.mean([a.elapsed_time(b) for a, b in ev])) * 1e3
+    del Kmean_bf
+    step.rebuild()                       # leave the fp32 selection in place
     # ... and a verification pass over a 7-node binary token tree instead of the chain
     step.tree_pass()
     torch.cuda.synchronize()
@@ -344,6 +358,7 @@ def main():
         "step_us_min": round(float(np.min(step_us)), 1),
         "extra": {"decode_attn_indexed_us_per_step": round(indexed_us, 1),
                   "decode_attn_tree7_us_per_step": round(tree_us, 1),
+                  "chunk_topk_gather_bf16_table_us_per_step": round(rebuild_bf16_us, 1),
                   "decode_attn_full_cold_us_per_layer": None if cold_us is None else round(cold_us, 1)},
         "roofline": {"bound": "hbm", "kernel": "attn_split_kernel (tf_decode_attn_full)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -20,6 +20,8 @@
  * and the verification pass for a token tree instead of a chain (Sec. 5.3.3, compatibility with
  * tree-based speculative decoding):
  *   tf_decode_attn_tree       tf_decode_attn_full with a per-query mask over the speculated tokens
+ * and a half-size variant of the average-key table:
+ *   tf_chunk_summarize_bf16, tf_chunk_topk_gather_bf16
  *
  * Conventions (all calls)
  *   - Every data pointer is a DEVICE pointer owned by the caller (the only host pointers are
@@ -126,6 +128,24 @@ int tf_chunk_topk_gather(const void *q_r, const float *Kmean, int64_t M_cap, con
                          const int32_t *n_chunks, int64_t n_chunks_all, int32_t k_chunks,
                          int32_t *out_idx, float *out_score, void *Kr, void *Vr,
                          const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_chunk_summarize_bf16 / tf_chunk_topk_gather_bf16 -- the same two operations (Sec. 4.1) with
+ * the average-key table held in bf16: half the table's memory and half the scoring traffic.
+ *   Kmean_bf16[b,h,m,:] = the fp32 mean of tf_chunk_summarize rounded to bf16 (nearest even);
+ *   scores are fp32 dot products of q_r with the widened bf16 entries; everything else
+ *   (selection order, ties, gather, arguments, workspace size, errors) as in the fp32 calls.
+ * A table written by tf_chunk_summarize_bf16 must be read by tf_chunk_topk_gather_bf16.
+ * Rounding the averages moves scores by up to ~4e-4 at these magnitudes, so the chunks chosen
+ * near the k-th score can differ from those the fp32 table selects.
+ * ------------------------------------------------------------------------------------- */
+int tf_chunk_summarize_bf16(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t first_chunk,
+                            int64_t n_chunks, void *Kmean, int64_t M_cap, void *stream);
+int tf_chunk_topk_gather_bf16(const void *q_r, const void *Kmean, int64_t M_cap, const void *K,
+                              const void *V, const tf_kv_desc *kd, int32_t chunk,
+                              const int32_t *n_chunks, int64_t n_chunks_all, int32_t k_chunks,
+                              int32_t *out_idx, float *out_score, void *Kr, void *Vr,
+                              const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * tf_decode_attn_full -- Algorithm 1, "Run M_p with full cache C_p": attention of the

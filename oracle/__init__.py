@@ -11,8 +11,10 @@ from .tf_oracle import (  # noqa: F401
     attention_tree,
     build_oracle,
     chunk_mean,
+    chunk_mean_bf16,
     gather,
     kv_append,
     num_threads,
     retrieve,
+    round_to_bf16,
 )

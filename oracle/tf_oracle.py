@@ -90,6 +90,21 @@ def chunk_mean(K, c: int) -> np.ndarray:
     return out
 
 
+def round_to_bf16(x) -> np.ndarray:
+    """Round float64 values to the nearest bf16 value (8 significant bits, ties to even), returned
+    as float64. Written from the format's definition: x = m * 2^e with 0.5 <= |m| < 1, m is
+    rounded to a multiple of 2^-8. (Finite, normal-range values only.)"""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)
+    return np.ldexp(np.rint(m * 256.0), e - 8)
+
+
+def chunk_mean_bf16(K, c: int) -> np.ndarray:
+    """Average keys held in bf16 (variant of Sec. 4.1's average-key table): the exact chunk mean,
+    rounded once to bf16. Returned as float64 [B,H,M,d] holding bf16-representable values."""
+    return round_to_bf16(chunk_mean(K, c))
+
+
 def retrieve(q_r, Kmean, k: int, n_chunks=None):
     """q_r [B,H,d] uint16(bf16), Kmean f64 [B,H,M,d] -> (scores f64 [B,H,M], idx int32 [B,H,k])."""
     q_r = _u16(q_r)

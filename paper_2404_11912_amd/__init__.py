@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     tf_decode_attn_indexed_workspace_bytes,
     tf_kv_append,
     tf_decode_attn_tree,
+    tf_chunk_summarize_bf16,
+    tf_chunk_topk_gather_bf16,
     tf_decode_attn_full_workspace_bytes,
     tf_decode_attn_retrieval,
     tf_decode_attn_retrieval_workspace_bytes,

@@ -28,6 +28,7 @@ EXPORTS = (
     "tf_spec_accept_workspace_bytes", "tf_spec_accept",
     "tf_decode_attn_indexed_workspace_bytes", "tf_decode_attn_indexed", "tf_kv_append",
     "tf_decode_attn_tree",
+    "tf_chunk_summarize_bf16", "tf_chunk_topk_gather_bf16",
 )
 
 
@@ -65,11 +66,15 @@ def load_library() -> ctypes.CDLL:
     lib.tf_set_option.argtypes = [ctypes.c_char_p, i64]
     lib.tf_chunk_summarize.restype = ctypes.c_int
     lib.tf_chunk_summarize.argtypes = [vp, dp, i32, i64, i64, vp, i64, vp]
+    lib.tf_chunk_summarize_bf16.restype = ctypes.c_int
+    lib.tf_chunk_summarize_bf16.argtypes = lib.tf_chunk_summarize.argtypes
     lib.tf_chunk_topk_gather_workspace_bytes.restype = sz
     lib.tf_chunk_topk_gather_workspace_bytes.argtypes = [i32, i32, i64, i32]
     lib.tf_chunk_topk_gather.restype = ctypes.c_int
     lib.tf_chunk_topk_gather.argtypes = [vp, vp, i64, vp, vp, dp, i32, vp, i64, i32, vp, vp, vp, vp, dp,
                                          vp, sz, vp]
+    lib.tf_chunk_topk_gather_bf16.restype = ctypes.c_int
+    lib.tf_chunk_topk_gather_bf16.argtypes = lib.tf_chunk_topk_gather.argtypes
     for name in ("tf_decode_attn_full", "tf_decode_attn_retrieval"):
         getattr(lib, name + "_workspace_bytes").restype = sz
         getattr(lib, name + "_workspace_bytes").argtypes = [i32, i32, i64, i32]
@@ -138,19 +143,32 @@ def tf_set_option(name: str, value: int) -> None:
     _check("tf_set_option", load_library().tf_set_option(name.encode(), int(value)))
 
 
-def tf_chunk_summarize(K, chunk: int, Kmean, first_chunk: int = 0, n_chunks: int | None = None, stream=None):
+def tf_chunk_summarize_bf16(K, chunk: int, Kmean, first_chunk: int = 0, n_chunks: int | None = None, stream=None):
+    """tf_chunk_summarize with a bf16 table: the fp32 mean rounded to bf16."""
+    return tf_chunk_summarize(K, chunk, Kmean, first_chunk, n_chunks, stream, _name="tf_chunk_summarize_bf16")
+
+
+def tf_chunk_topk_gather_bf16(q_r, Kmean, K, V, chunk: int, k_chunks: int, out_idx, Kr=None, Vr=None,
+                              out_score=None, n_chunks=None, n_chunks_all: int | None = None, ws=None, stream=None):
+    """tf_chunk_topk_gather over a bf16 average-key table."""
+    return tf_chunk_topk_gather(q_r, Kmean, K, V, chunk, k_chunks, out_idx, Kr, Vr, out_score, n_chunks,
+                                n_chunks_all, ws, stream, _name="tf_chunk_topk_gather_bf16")
+
+
+def tf_chunk_summarize(K, chunk: int, Kmean, first_chunk: int = 0, n_chunks: int | None = None, stream=None,
+                       _name: str = "tf_chunk_summarize"):
     """Kmean[b,h,m,:] = mean of K[b,h,m*chunk:(m+1)*chunk,:] for m in [first_chunk, first_chunk+n_chunks)."""
     lib = load_library()
-    _need(Kmean, torch.float32, "Kmean")
+    _need(Kmean, torch.bfloat16 if _name.endswith("_bf16") else torch.float32, "Kmean")
     d = kv_desc(K)
     if Kmean.dim() != 4 or Kmean.shape[0] != d.batch or Kmean.shape[1] != d.heads or Kmean.shape[3] != d.head_dim:
         raise ValueError("Kmean must be [B,H,M_cap,d]")
     M_cap = Kmean.shape[2]
     if n_chunks is None:
         n_chunks = min(M_cap, K.shape[2] // chunk) - first_chunk
-    _check("tf_chunk_summarize",
-           lib.tf_chunk_summarize(_ptr(K), ctypes.byref(d), int(chunk), int(first_chunk), int(n_chunks),
-                                  _ptr(Kmean), int(M_cap), _stream(stream)))
+    _check(_name,
+           getattr(lib, _name)(_ptr(K), ctypes.byref(d), int(chunk), int(first_chunk), int(n_chunks),
+                               _ptr(Kmean), int(M_cap), _stream(stream)))
     return Kmean
 
 
@@ -159,11 +177,12 @@ def tf_chunk_topk_gather_workspace_bytes(batch: int, heads: int, n_chunks_all: i
 
 
 def tf_chunk_topk_gather(q_r, Kmean, K, V, chunk: int, k_chunks: int, out_idx, Kr=None, Vr=None,
-                         out_score=None, n_chunks=None, n_chunks_all: int | None = None, ws=None, stream=None):
+                         out_score=None, n_chunks=None, n_chunks_all: int | None = None, ws=None, stream=None,
+                         _name: str = "tf_chunk_topk_gather"):
     """Score chunks by q_r . Kmean, keep the k_chunks best (descending), gather their K/V into Kr/Vr."""
     lib = load_library()
     _need(q_r, torch.bfloat16, "q_r")
-    _need(Kmean, torch.float32, "Kmean")
+    _need(Kmean, torch.bfloat16 if _name.endswith("_bf16") else torch.float32, "Kmean")
     _need(out_idx, torch.int32, "out_idx")
     d = kv_desc(K)
     kv_desc(V)
@@ -184,12 +203,12 @@ def tf_chunk_topk_gather(q_r, Kmean, K, V, chunk: int, k_chunks: int, out_idx, K
             raise ValueError("Kr and Vr must share shape and strides")
     if ws is None:
         ws = workspace(tf_chunk_topk_gather_workspace_bytes(d.batch, d.heads, n_chunks_all, k_chunks), K.device)
-    _check("tf_chunk_topk_gather",
-           lib.tf_chunk_topk_gather(_ptr(q_r), _ptr(Kmean), int(M_cap), _ptr(K), _ptr(V), ctypes.byref(d),
-                                    int(chunk), _ptr(n_chunks), int(n_chunks_all), int(k_chunks),
-                                    _ptr(out_idx), _ptr(out_score), _ptr(Kr), _ptr(Vr),
-                                    ctypes.byref(rd) if rd is not None else None,
-                                    _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+    _check(_name,
+           getattr(lib, _name)(_ptr(q_r), _ptr(Kmean), int(M_cap), _ptr(K), _ptr(V), ctypes.byref(d),
+                               int(chunk), _ptr(n_chunks), int(n_chunks_all), int(k_chunks),
+                               _ptr(out_idx), _ptr(out_score), _ptr(Kr), _ptr(Vr),
+                               ctypes.byref(rd) if rd is not None else None,
+                               _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
     return out_idx
 
 

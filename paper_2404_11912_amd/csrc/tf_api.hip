@@ -5,11 +5,11 @@
 #include "tf_common.hpp"
 
 namespace tf {
-int summarize_launch(const void *, const tf_kv_desc *, int32_t, int64_t, int64_t, float *, int64_t, void *);
+int summarize_launch(const void *, const tf_kv_desc *, int32_t, int64_t, int64_t, void *, int64_t, void *, bool);
 size_t topk_workspace_bytes(int32_t, int32_t, int64_t, int32_t);
-int topk_gather_launch(const void *, const float *, int64_t, const void *, const void *, const tf_kv_desc *, int32_t,
+int topk_gather_launch(const void *, const void *, int64_t, const void *, const void *, const tf_kv_desc *, int32_t,
                        const int32_t *, int64_t, int32_t, int32_t *, float *, void *, void *, const tf_kv_desc *,
-                       void *, size_t, void *);
+                       void *, size_t, void *, bool);
 size_t attn_workspace_bytes(int32_t, int32_t, int64_t, int32_t, bool);
 size_t attn_indexed_workspace_bytes(int32_t, int32_t, int32_t, int32_t, int64_t, int32_t);
 int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, const int32_t *, int64_t, int32_t,
@@ -48,7 +48,12 @@ int tf_set_option(const char *name, int64_t value) {
 
 int tf_chunk_summarize(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t first_chunk, int64_t n_chunks,
                        float *Kmean, int64_t M_cap, void *stream) {
-    return tf::summarize_launch(K, kd, chunk, first_chunk, n_chunks, Kmean, M_cap, stream);
+    return tf::summarize_launch(K, kd, chunk, first_chunk, n_chunks, Kmean, M_cap, stream, false);
+}
+
+int tf_chunk_summarize_bf16(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t first_chunk,
+                            int64_t n_chunks, void *Kmean, int64_t M_cap, void *stream) {
+    return tf::summarize_launch(K, kd, chunk, first_chunk, n_chunks, Kmean, M_cap, stream, true);
 }
 
 size_t tf_chunk_topk_gather_workspace_bytes(int32_t batch, int32_t heads, int64_t n_chunks_all, int32_t k_chunks) {
@@ -60,7 +65,15 @@ int tf_chunk_topk_gather(const void *q_r, const float *Kmean, int64_t M_cap, con
                          int32_t k_chunks, int32_t *out_idx, float *out_score, void *Kr, void *Vr,
                          const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream) {
     return tf::topk_gather_launch(q_r, Kmean, M_cap, K, V, kd, chunk, n_chunks, n_chunks_all, k_chunks, out_idx,
-                                  out_score, Kr, Vr, rd, ws, ws_bytes, stream);
+                                  out_score, Kr, Vr, rd, ws, ws_bytes, stream, false);
+}
+
+int tf_chunk_topk_gather_bf16(const void *q_r, const void *Kmean, int64_t M_cap, const void *K, const void *V,
+                              const tf_kv_desc *kd, int32_t chunk, const int32_t *n_chunks, int64_t n_chunks_all,
+                              int32_t k_chunks, int32_t *out_idx, float *out_score, void *Kr, void *Vr,
+                              const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream) {
+    return tf::topk_gather_launch(q_r, Kmean, M_cap, K, V, kd, chunk, n_chunks, n_chunks_all, k_chunks, out_idx,
+                                  out_score, Kr, Vr, rd, ws, ws_bytes, stream, true);
 }
 
 size_t tf_decode_attn_full_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G) {

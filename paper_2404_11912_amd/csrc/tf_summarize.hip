@@ -1,5 +1,5 @@
 // tf_chunk_summarize: the average key of every KV chunk (Sec. 4.1, "the average key cache
-// within each chunk"), fp32 output.
+// within each chunk"), fp32 output (or, as a variant, the fp32 mean rounded to bf16).
 //
 // Pure HBM streaming: K is read once (256 B per token), 512 B are written per chunk. A wave
 // owns 4 chunks at a time: lane (r,s) accumulates dims 8r..8r+8 of chunk s over the chunk's
@@ -19,10 +19,11 @@ struct SumParams {
     int32_t H, chunk;
     int64_t first_chunk, n_chunks;
     int64_t blocks_per_bh;
-    float *Kmean;
+    void *Kmean;  // fp32 or bf16 [BH][M_cap][128]
     int64_t M_cap;
 };
 
+template <bool kBf16Out>
 __global__ __launch_bounds__(kSumWaves * 64) void chunk_summarize_kernel(const SumParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, s = lane >> 4;
@@ -57,15 +58,25 @@ __global__ __launch_bounds__(kSumWaves * 64) void chunk_summarize_kernel(const S
                     acc[7] += bf16hi(v[u].w);
                 }
         }
-        float *dst = p.Kmean + (bh * p.M_cap + m) * kHeadDim + r * 8;
+        const int64_t off = (bh * p.M_cap + m) * kHeadDim + r * 8;
         const float fc = (float)c;  // correctly rounded division: exact for power-of-two chunks
-        *reinterpret_cast<float4 *>(dst) = make_float4(acc[0] / fc, acc[1] / fc, acc[2] / fc, acc[3] / fc);
-        *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4] / fc, acc[5] / fc, acc[6] / fc, acc[7] / fc);
+        if constexpr (kBf16Out) {
+            uint4 o;
+            o.x = f32_to_bf16(acc[0] / fc) | (f32_to_bf16(acc[1] / fc) << 16);
+            o.y = f32_to_bf16(acc[2] / fc) | (f32_to_bf16(acc[3] / fc) << 16);
+            o.z = f32_to_bf16(acc[4] / fc) | (f32_to_bf16(acc[5] / fc) << 16);
+            o.w = f32_to_bf16(acc[6] / fc) | (f32_to_bf16(acc[7] / fc) << 16);
+            st16(static_cast<uint16_t *>(p.Kmean) + off, o);
+        } else {
+            float *dst = static_cast<float *>(p.Kmean) + off;
+            *reinterpret_cast<float4 *>(dst) = make_float4(acc[0] / fc, acc[1] / fc, acc[2] / fc, acc[3] / fc);
+            *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4] / fc, acc[5] / fc, acc[6] / fc, acc[7] / fc);
+        }
     }
 }
 
 int summarize_launch(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t first_chunk, int64_t n_chunks,
-                     float *Kmean, int64_t M_cap, void *stream) {
+                     void *Kmean, int64_t M_cap, void *stream, bool mean_bf16) {
     if (!K || !Kmean) return TF_ERR_INVALID_ARG;
     int rc = check_desc(kd);
     if (rc != TF_OK) return rc;
@@ -89,8 +100,11 @@ int summarize_launch(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t
     p.Kmean = Kmean;
     p.M_cap = M_cap;
     if (p.blocks_per_bh * BH >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(chunk_summarize_kernel, dim3((unsigned)(p.blocks_per_bh * BH)), dim3(kSumWaves * 64), 0,
-                       static_cast<hipStream_t>(stream), p);
+    const dim3 grid((unsigned)(p.blocks_per_bh * BH));
+    if (mean_bf16)
+        hipLaunchKernelGGL(chunk_summarize_kernel<true>, grid, dim3(kSumWaves * 64), 0, static_cast<hipStream_t>(stream), p);
+    else
+        hipLaunchKernelGGL(chunk_summarize_kernel<false>, grid, dim3(kSumWaves * 64), 0, static_cast<hipStream_t>(stream), p);
     return hip_status(hipGetLastError());
 }
 

@@ -27,7 +27,7 @@ int set_score_option(int64_t v) {
 
 struct ScoreParams {
     const uint16_t *q_r;
-    const float *Kmean;
+    const void *Kmean;  // fp32, or bf16 for the bf16 scoring kernel
     int64_t M_cap;
     const int32_t *n_chunks;
     int32_t n_all, H;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void chunk_score_kernel(const ScoreParams p) {
         q[j][2] = bf16lo(u.y);
         q[j][3] = bf16hi(u.y);
     }
-    const float *base = p.Kmean + bh * p.M_cap * kHeadDim + 4 * e;
+    const float *base = static_cast<const float *>(p.Kmean) + bh * p.M_cap * kHeadDim + 4 * e;
     float *out = p.scores + bh * p.score_stride;
 
     // the 4 waves interleave 16-row steps over the workgroup's contiguous range (one stream
@@ -105,6 +105,82 @@ __global__ __launch_bounds__(256) void chunk_score_kernel(const ScoreParams p) {
 
     if (left > 0) {
         float4 va[8], vb[8];
+        int m0 = m_begin;
+        load(m0, va);
+        while (left > 2) {
+            load(m0 + 64, vb);
+            finish(m0, va);
+            load(m0 + 128, va);
+            finish(m0 + 64, vb);
+            m0 += 128;
+            left -= 2;
+        }
+        if (left == 2) {
+            load(m0 + 64, vb);
+            finish(m0, va);
+            finish(m0 + 64, vb);
+        } else {
+            finish(m0, va);
+        }
+    }
+}
+
+// The same scoring over a bf16 average-key table (256 B per chunk, half the traffic): 16 lanes per
+// row, 4 whole rows per load instruction, lane (e, w) = (lane % 16, lane / 16) holds dims 8e..8e+8
+// of row w, 8 fp32 FMAs on the widened values per load and four shuffles per row.
+__global__ __launch_bounds__(256) void chunk_score_bf16_kernel(const ScoreParams p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int e = lane & 15, w = lane >> 4;
+    const int blk = blockIdx.x % p.blocks_per_bh;
+    const int64_t bh = blockIdx.x / p.blocks_per_bh;
+    const int b = (int)(bh / p.H);
+    int n = p.n_chunks ? p.n_chunks[b] : p.n_all;
+    n = min(max(n, 0), p.n_all);
+    const int last_row = max(n - 1, 0);
+
+    float q[8];
+    {
+        const uint4 u = ld16(p.q_r + bh * kHeadDim + 8 * e);
+        q[0] = bf16lo(u.x); q[1] = bf16hi(u.x); q[2] = bf16lo(u.y); q[3] = bf16hi(u.y);
+        q[4] = bf16lo(u.z); q[5] = bf16hi(u.z); q[6] = bf16lo(u.w); q[7] = bf16hi(u.w);
+    }
+    const uint16_t *base = static_cast<const uint16_t *>(p.Kmean) + bh * p.M_cap * kHeadDim + 8 * e;
+    float *out = p.scores + bh * p.score_stride;
+
+    const int m_begin = blk * 64 * p.iters + wave * 16;
+    const int m_end = min((blk + 1) * 64 * p.iters, p.n_all);
+    int left = (m_end - m_begin + 63) / 64;  // 16-row steps of this wave
+
+    auto load = [&](int m0, uint4(&v)[4]) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            v[rr] = ld16_stream(base + (int64_t)min(m0 + 4 * rr + w, last_row) * kHeadDim);
+    };
+    auto finish = [&](int m0, const uint4(&v)[4]) {
+        float mine = 0.f;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            float a = q[0] * bf16lo(v[rr].x);
+            a = fmaf(q[1], bf16hi(v[rr].x), a);
+            a = fmaf(q[2], bf16lo(v[rr].y), a);
+            a = fmaf(q[3], bf16hi(v[rr].y), a);
+            a = fmaf(q[4], bf16lo(v[rr].z), a);
+            a = fmaf(q[5], bf16hi(v[rr].z), a);
+            a = fmaf(q[6], bf16lo(v[rr].w), a);
+            a = fmaf(q[7], bf16hi(v[rr].w), a);
+            a += __shfl_xor(a, 1, kWave);
+            a += __shfl_xor(a, 2, kWave);
+            a += __shfl_xor(a, 4, kWave);
+            a += __shfl_xor(a, 8, kWave);
+            if (e == rr) mine = a;
+        }
+        // lane e < 4 stores row m0 + 4e + w
+        const int m = m0 + 4 * e + w;
+        if (e < 4 && m < p.n_all) out[m] = m < n ? mine : -INFINITY;
+    };
+
+    if (left > 0) {
+        uint4 va[4], vb[4];
         int m0 = m_begin;
         load(m0, va);
         while (left > 2) {
@@ -326,10 +402,10 @@ size_t topk_workspace_bytes(int32_t batch, int32_t heads, int64_t n_chunks_all, 
     return ((size_t)batch * heads * score_stride_of(n_chunks_all) + 4) * sizeof(float);
 }
 
-int topk_gather_launch(const void *q_r, const float *Kmean, int64_t M_cap, const void *K, const void *V,
+int topk_gather_launch(const void *q_r, const void *Kmean, int64_t M_cap, const void *K, const void *V,
                        const tf_kv_desc *kd, int32_t chunk, const int32_t *n_chunks, int64_t n_chunks_all,
                        int32_t k_chunks, int32_t *out_idx, float *out_score, void *Kr, void *Vr,
-                       const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream) {
+                       const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream, bool mean_bf16) {
     if (!q_r || !Kmean || !out_idx) return TF_ERR_INVALID_ARG;
     int rc = check_desc(kd);
     if (rc != TF_OK) return rc;
@@ -347,7 +423,7 @@ int topk_gather_launch(const void *q_r, const float *Kmean, int64_t M_cap, const
     if (n_chunks_all > M_cap || k_chunks > n_chunks_all) return TF_ERR_INVALID_ARG;
     if (n_chunks_all > ((int64_t)1 << 30)) return TF_ERR_UNSUPPORTED;
     if (n_chunks_all * chunk > kd->capacity) return TF_ERR_INVALID_ARG;
-    if (!aligned(q_r, 8) || !aligned(Kmean, 16)) return TF_ERR_INVALID_ARG;
+    if (!aligned(q_r, mean_bf16 ? 16 : 8) || !aligned(Kmean, 16)) return TF_ERR_INVALID_ARG;
     if (!ws || !aligned(ws, 256) ||
         ws_bytes < topk_workspace_bytes(kd->batch, kd->heads, n_chunks_all, k_chunks))
         return TF_ERR_WORKSPACE;
@@ -372,7 +448,10 @@ int topk_gather_launch(const void *q_r, const float *Kmean, int64_t M_cap, const
     sp.scores = static_cast<float *>(ws);
     sp.score_stride = score_stride_of(n_chunks_all);
     if (sp.blocks_per_bh * BH >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(chunk_score_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
+    if (mean_bf16)
+        hipLaunchKernelGGL(chunk_score_bf16_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
+    else
+        hipLaunchKernelGGL(chunk_score_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
 
     hipLaunchKernelGGL(topk_select_kernel, dim3((unsigned)BH), dim3(kSelThreads), 0, st, sp.scores,
                        sp.score_stride, n_chunks, (int)n_chunks_all, (int)kd->heads, (int)k_chunks, out_idx,

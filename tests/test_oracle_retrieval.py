@@ -161,3 +161,23 @@ def test_full_budget_retrieval_attention_equals_full_attention(c):
     O_r, L_r, _ = oracle.attention(Q, Kr, Vr, scale=1.0, causal=False)
     assert np.max(np.abs(O_full - O_r)) < 1e-12
     assert np.max(np.abs(L_full - L_r)) < 1e-12
+
+
+def test_round_to_bf16_matches_a_library_conversion():
+    """The bf16 average-key variant rounds the exact mean once to bf16. The rounding helper is
+    pinned against torch's float32 -> bfloat16 conversion (round to nearest even) on values that
+    are exact in float32, and on hand-made ties."""
+    import torch
+    rng = np.random.default_rng(5)
+    x32 = (rng.standard_normal(200000) * np.exp(rng.uniform(-20, 20, 200000))).astype(np.float32)
+    want = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = oracle.round_to_bf16(x32.astype(np.float64))
+    assert np.array_equal(got, want)
+    # ties: 1 + 2^-8 lies halfway between 1 and 1 + 2^-7 -> even (1); 1 + 3*2^-8 -> 1 + 2^-6
+    assert oracle.round_to_bf16(np.array([1 + 2.0 ** -8]))[0] == 1.0
+    assert oracle.round_to_bf16(np.array([1 + 3 * 2.0 ** -8]))[0] == 1 + 2.0 ** -6
+    assert oracle.round_to_bf16(np.array([-(1 + 2.0 ** -8 + 2.0 ** -30)]))[0] == -(1 + 2.0 ** -7)
+    assert oracle.round_to_bf16(np.array([0.0]))[0] == 0.0
+    # the table itself: a chunk of identical keys keeps that key; c = 1 reproduces K
+    K = bf16_u16(rng.standard_normal((1, 2, 16, 128)))
+    assert np.array_equal(oracle.chunk_mean_bf16(K, 1), u16_f64(K))
