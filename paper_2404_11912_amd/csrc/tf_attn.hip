@@ -1,14 +1,15 @@
-// tf_decode_attn_full / tf_decode_attn_retrieval / tf_decode_attn_indexed: attention of G <= 8
-// speculated query tokens over a long bf16 KV cache (Algorithm 1: the M_p(C_p, ...) verification
-// pass and the M_p(C_r, ...) drafting pass; the indexed form reads the draft cache through the
-// chunk indices of Sec. 4.1 instead of a gathered copy).
+// tf_decode_attn_full / tf_decode_attn_retrieval / tf_decode_attn_indexed / tf_decode_attn_tree:
+// attention of G <= 8 speculated query tokens over a long bf16 KV cache (Algorithm 1: the
+// M_p(C_p, ...) verification pass and the M_p(C_r, ...) drafting pass; the indexed form reads the
+// draft cache through the chunk indices of Sec. 4.1 instead of a gathered copy; the tree form
+// replaces the causal triangle over the G tokens by an ancestor mask, Sec. 5.3.3).
 //
 // Design (gfx950, wave64): flash-decoding. The KV sequence of every (b,h) is cut into
 // `nsplit` contiguous ranges, one 256-thread workgroup each; its 4 waves walk interleaved
 // 16-token tiles, so the workgroup streams K and V front to back. Per tile and wave:
 //   * K rows arrive as MFMA A-operands (lane (r,s): token r, dims 32kk+8s..+8) and four
 //     v_mfma_f32_16x16x32_bf16 give S^T[token, query] against the Q operand, which lives in
-//     LDS and is re-read per tile (16 VGPRs fewer: a third wave per SIMD);
+//     LDS and is re-read per tile (16 VGPRs fewer);
 //   * the accumulator layout (lane (r,s), reg i = token 4s+i, query r) is exactly the
 //     A-operand layout of v_mfma_f32_16x16x4_f32, so P = exp2(S - m) feeds the PV product
 //     with no data movement; V rows arrive fully coalesced (lane (r,s): token 4s+i, dims
@@ -19,7 +20,10 @@
 //   * all K/V loads carry the nt bit: the cache is touched once per pass and must not displace
 //     anything in L2 / the last-level cache (+15% bandwidth measured).
 // The 4 waves merge (m, l, O) through LDS and write one fp32 partial per split; a small
-// second kernel merges the splits by log-sum-exp and normalises.
+// second kernel merges the splits by log-sum-exp and normalises. The host plans the splits so
+// that, where batch x heads allows, exactly one workgroup runs per CU (see plan_splits).
+// The 16 columns of the QK^T MFMA hold up to 16 query rows, so the query heads of a
+// grouped-query KV head share its pass; head dim 128 or 64.
 #include <type_traits>
 
 #include "tf_common.hpp"
