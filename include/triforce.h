@@ -91,7 +91,7 @@ const char *tf_status_string(int code); /* static string, never NULL */
 int tf_set_option(const char *name, int64_t value);
 
 /* ---------------------------------------------------------------------------------------
- * tf_chunk_summarize -- Sec. 4.1: "the average key cache within each chunk".
+ * tf_chunk_summarize -- Sec. 4.1: every chunk of the KV cache is summarised by the mean of its keys.
  *   Kmean[b,h,m,:] = (1/chunk) * sum_{i<chunk} K[b,h,m*chunk+i,:]   for
  *   m in [first_chunk, first_chunk+n_chunks), every (b,h). fp32 sums of bf16 keys.
  *   K      in   bf16, described by kd; (first_chunk+n_chunks)*chunk <= kd->capacity
@@ -148,7 +148,7 @@ int tf_chunk_topk_gather_bf16(const void *q_r, const void *Kmean, int64_t M_cap,
                               const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * tf_decode_attn_full -- Algorithm 1, "Run M_p with full cache C_p": attention of the
+ * tf_decode_attn_full -- Algorithm 1, the pass of M_p over the full cache C_p: attention of the
  * G = gamma+1 speculated query tokens of one layer over the whole KV cache.
  *   len[b] = kv_len ? kv_len[b] : kv_len_all (kv_len_all is always an upper bound of len[b]
  *   and <= kd->capacity). For every (b,h,g), with n_g = causal ? len[b]-G+1+g : len[b]
@@ -170,8 +170,8 @@ int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv
                         void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * tf_decode_attn_tree -- verification of a speculated token TREE (Sec. 5.3.3 "Compatibility with
- * Tree-based Speculative Decoding"): tf_decode_attn_full with the causal triangle replaced by an
+ * tf_decode_attn_tree -- verification of a speculated token TREE (Sec. 5.3.3, the combination with
+ * tree-based speculative decoding): tf_decode_attn_full with the causal triangle replaced by an
  * ancestor mask. The G speculated tokens are the last G rows of the cache, in any order that
  * puts parents before children; query g sees every row t < len[b]-G (the context) and, of the
  * speculated rows, row len[b]-G+j iff bit j of tail_mask[g] is set (normally its ancestors and
@@ -188,7 +188,7 @@ int tf_decode_attn_tree(const void *Q, const void *K, const void *V, const tf_kv
                         void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * tf_decode_attn_retrieval -- Algorithm 1, "Run M_p with retrieval cache C_r": the same
+ * tf_decode_attn_retrieval -- Algorithm 1, the pass of M_p over the retrieval cache C_r: the same
  * attention over the gathered retrieval cache (K, V are Kr, Vr; kv_len is the number of valid
  * cache rows, budget plus any tokens the caller appended). Same arguments and semantics as
  * tf_decode_attn_full; tuned for short caches (launch-latency regime).
@@ -201,8 +201,8 @@ int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const 
                              void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * tf_decode_attn_indexed -- gather-free drafting (Algorithm 1, "Run M_p with retrieval cache
- * C_r"; Sec. 4.1 chunk selection): the same attention, over a draft cache that is never
+ * tf_decode_attn_indexed -- gather-free drafting (Algorithm 1, the pass of M_p over the retrieval
+ * cache C_r; Sec. 4.1 chunk selection): the same attention, over a draft cache that is never
  * materialised. For every (b,h) the draft cache is the concatenation of
  *   (1) the chunks idx[b,h,0..k_chunks) of the cache (K,V,kd): chunk j contributes the rows
  *       idx[b,h,j]*chunk .. idx[b,h,j]*chunk+chunk-1; negative entries (and chunks reaching
@@ -227,8 +227,8 @@ int tf_decode_attn_indexed(const void *Q, const void *K, const void *V, const tf
                            float *LSE, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * tf_kv_append -- cache update of Algorithm 1 ("Update C_r, C_q based on the accepted
- * tokens"; Sec. 4.3: new tokens overwrite the least important entries of the retrieval cache).
+ * tf_kv_append -- cache update of Algorithm 1 (its last step, the update of C_r and C_q with the
+ * accepted tokens; Sec. 4.3: new tokens overwrite the least important entries of the retrieval cache).
  *   K[b,h,p[b]+i,:] = Knew[b,h,i,:] (same for V) for i < n, p[b] = pos ? pos[b] : pos_all.
  *   Knew, Vnew in  bf16 [batch, heads, n, 128] contiguous
  *   K, V       out bf16, described by kd; bit-exact row copies; other rows untouched
@@ -242,7 +242,7 @@ int tf_kv_append(const void *Knew, const void *Vnew, int32_t n, void *K, void *V
                  const tf_kv_desc *kd, const int32_t *pos, int64_t pos_all, void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * tf_spec_accept -- Algorithm 1, Verify / Correct / "sample next token" lines, i.e. the
+ * tf_spec_accept -- Algorithm 1, the Verify, Correct and next-token sampling steps, i.e. the
  * standard lossless speculative-sampling rule (Sec. 4.2 "Correctness"). One sequence per b,
  * gamma = G-1 drafted tokens. With p_i = softmax(target_logits[b,i]/T),
  * q_i = softmax(draft_logits[b,i]/T) (computed in fp64):

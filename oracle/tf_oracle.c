@@ -14,7 +14,7 @@
  *   orc_attention   model forward over a KV cache (Algorithm 1, the M_p(C_p, ...) and
  *                   M_p(C_r, ...) steps): standard scaled-dot-product attention, the
  *                   plain definition written out.
- *   orc_chunk_mean  "average key cache within each chunk" (Sec. 4.1).
+ *   orc_chunk_mean  the mean of the keys of every chunk (Sec. 4.1).
  *   orc_retrieve    score = query . average chunk key, keep the highest-scoring
  *                   chunks under a fixed budget, in descending importance
  *                   (Sec. 4.1, Sec. 4.3).

@@ -239,7 +239,7 @@ def attention_tree(Q, K, V, tail_mask, kv_len=None, scale: float = 1.0):
 
 
 def kv_append(Knew, Vnew, K, V, pos):
-    """Cache update (Algorithm 1, "Update C_r, C_q"; Sec. 4.3): returns copies of K, V with
+    """Cache update (last step of Algorithm 1; Sec. 4.3): returns copies of K, V with
     K[b,h,pos[b]+i] = Knew[b,h,i] (same for V); destination rows outside the cache are dropped."""
     Knew, Vnew, K, V = _u16(Knew), _u16(Vnew), _u16(K).copy(), _u16(V).copy()
     B, H, n, d = Knew.shape

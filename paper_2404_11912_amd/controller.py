@@ -20,7 +20,7 @@ from . import binding as tf
 @dataclass
 class RebuildPolicy:
     """When to rebuild the retrieval cache (Sec. 4.3): at a fixed stride of verification steps,
-    or when the rolling average acceptance rate of the verification level drops below a
+    or when the running mean of the acceptance rate at the verification level falls below a
     threshold. stride = 0 / threshold = 0 switch the respective trigger off."""
     stride: int = 0
     threshold: float = 0.0

@@ -1,5 +1,5 @@
-// tf_kv_append: write the K/V rows of newly decoded tokens into a cache (Sec. 4.3: "we overwrite
-// tokens with the least importance" for the retrieval cache; plain append for the full cache).
+// tf_kv_append: write the K/V rows of newly decoded tokens into a cache (Sec. 4.3: in the
+// retrieval cache they replace the least important entries; plain append for the full cache).
 // A strided row copy: one wave moves 4 rows of K and of V with 16-byte accesses (16 lanes per row;
 // rows of head_dim 64 use the first 8 of them).
 #include "tf_common.hpp"

@@ -1,5 +1,5 @@
-// tf_chunk_summarize: the average key of every KV chunk (Sec. 4.1, "the average key cache
-// within each chunk"), fp32 output (or, as a variant, the fp32 mean rounded to bf16).
+// tf_chunk_summarize: the average key of every KV chunk (Sec. 4.1: the keys of a chunk are
+// averaged), fp32 output (or, as a variant, the fp32 mean rounded to bf16).
 //
 // Pure HBM streaming: K is read once (256 B per token), 512 B are written per chunk. A wave
 // owns 4 chunks at a time: lane (r,s) accumulates dims 8r..8r+8 of chunk s over the chunk's
