@@ -190,3 +190,58 @@ def test_batch_with_per_sequence_lengths_at_a_batching_shape():
     say(f"[ragged 6x19k] indexed draft attention: max|dO|={ed:.2e} max|dLSE|={eld:.2e}; "
         f"top-k order identical on {int(same.sum())}/{B * H} units")
     assert ed <= ATTN_TOL and eld <= LSE_TOL
+
+
+@pytest.mark.parametrize("name,n_pairs", [("step128k", 64), ("batch4x64k", 16), ("extreme1m", 8)])
+def test_random_layer_head_pairs(name, n_pairs):
+    """Seeded random (layer, batch, head) units spread over all layers of a workload: the whole
+    layer runs on the device in the benchmark's launch configuration, the oracle checks the
+    sampled units (chunk means, selection per the tie-band rule, verification and draft attention)."""
+    w = synth.WORKLOADS[name]
+    rng = np.random.default_rng(4242 + w.index)
+    flat = rng.choice(w.L * w.B * w.H, size=n_pairs, replace=False)
+    by_layer = {}
+    for f in sorted(flat.tolist()):
+        l, rem = divmod(f, w.B * w.H)
+        by_layer.setdefault(l, []).append(divmod(rem, w.H))
+    say(f"case fullsize random pairs {name}: {n_pairs} units over layers {sorted(by_layer)}")
+    worst = dict(o=0.0, l=0.0, od=0.0, km=0.0)
+    for l, units in by_layer.items():
+        x = synth.make_workload_layer(w, l, DEV)
+        K, V, Q, q_r = x["K"], x["V"], x["Q"], x["q_r"]
+        B, H, N, d = K.shape
+        Kmean = torch.empty((B, H, w.M, d), dtype=torch.float32, device=DEV)
+        tf.tf_chunk_summarize(K, w.c, Kmean, 0, w.M)
+        idx = torch.empty((B, H, w.k), dtype=torch.int32, device=DEV)
+        tf.tf_chunk_topk_gather(q_r, Kmean, K, V, w.c, w.k, idx)
+        O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+        L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+        tf.tf_decode_attn_full(Q, K, V, O, L, causal=True)
+        Qd = Q[:, :, -w.G_d:, :].contiguous()
+        O_d = torch.empty(Qd.shape, dtype=torch.float32, device=DEV)
+        L_d = torch.empty(Qd.shape[:3], dtype=torch.float32, device=DEV)
+        tf.tf_decode_attn_indexed(Qd, K, V, idx, w.c, O_d, L_d, kv_len_all=N, recent_begin_all=N - w.G_d, causal=True)
+        torch.cuda.synchronize()
+        for (b, h) in units:
+            Ku, Vu = synth.as_u16(K[b:b + 1, h:h + 1]), synth.as_u16(V[b:b + 1, h:h + 1])
+            Qu, qu = synth.as_u16(Q[b:b + 1, h:h + 1]), synth.as_u16(q_r[b:b + 1, h:h + 1])
+            km = oracle.chunk_mean(Ku, w.c)
+            worst["km"] = max(worst["km"], float(np.max(np.abs(Kmean[b, h].cpu().numpy() - km[0, 0]))))
+            s, o_idx = oracle.retrieve(qu, km, w.k)
+            s, got = s[0, 0], idx[b, h].cpu().numpy()
+            tau = s[o_idx[0, 0, -1]]
+            assert len(set(got.tolist())) == w.k and got.min() >= 0 and got.max() < w.M
+            assert set(np.where(s > tau + TIE_BAND)[0].tolist()) <= set(got.tolist())
+            assert not (set(got.tolist()) & set(np.where(s < tau - TIE_BAND)[0].tolist()))
+            assert np.all(s[got][1:] <= s[got][:-1] + TIE_BAND)
+            Oo, Lo, _ = oracle.attention(Qu, Ku, Vu, scale=1.0, causal=True)
+            worst["o"] = max(worst["o"], float(np.max(np.abs(O[b, h].cpu().numpy() - Oo[0, 0]))))
+            worst["l"] = max(worst["l"], float(np.max(np.abs(L[b, h].cpu().numpy() - Lo[0, 0]))))
+            Od, _ = oracle.attention_indexed(np.ascontiguousarray(Qu[:, :, -w.G_d:, :]), Ku, Vu, got[None, None], w.c,
+                                             recent_begin=N - w.G_d, causal=True)[:2]
+            worst["od"] = max(worst["od"], float(np.max(np.abs(O_d[b, h].cpu().numpy() - Od[0, 0]))))
+        del x, K, V, Kmean
+        torch.cuda.empty_cache()
+    say(f"[{name} random pairs] max|dO| verify {worst['o']:.2e}, draft {worst['od']:.2e}; max|dLSE| {worst['l']:.2e}; "
+        f"chunk means {worst['km']:.1e}")
+    assert worst["o"] <= ATTN_TOL and worst["od"] <= ATTN_TOL and worst["l"] <= LSE_TOL and worst["km"] < 2e-6
