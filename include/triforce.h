@@ -53,12 +53,12 @@ extern "C" {
 
 #define TF_OK 0
 #define TF_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, inconsistent shapes      */
-#define TF_ERR_UNSUPPORTED (-2) /* head_dim not supported, G > 8, k_chunks > 2048, ...        */
+#define TF_ERR_UNSUPPORTED (-2) /* head_dim not supported, G > 16, k_chunks > 2048, ...       */
 #define TF_ERR_WORKSPACE (-3)   /* workspace missing, misaligned or too small                */
 #define TF_ERR_HIP (-4)         /* a HIP runtime call (kernel launch) reported an error      */
 
 #define TF_HEAD_DIM 128
-#define TF_MAX_QUERIES 8     /* G = gamma + 1 queries per attention call                     */
+#define TF_MAX_QUERIES 16    /* G = gamma + 1 queries per attention call (8 with a tree mask) */
 #define TF_MAX_K_CHUNKS 2048 /* chunks kept by one tf_chunk_topk_gather call                 */
 #define TF_MAX_SPEC 16       /* G of tf_spec_accept                                          */
 
@@ -69,7 +69,7 @@ extern "C" {
  * aligned (strides multiples of 8 elements). K and V of one call share one descriptor.
  * Grouped-query attention: with q_group > 1 the attention calls take Q, O of
  * [batch, heads*q_group, G, head_dim] and LSE of [batch, heads*q_group, G]; query head q uses KV
- * head q / q_group. G * q_group <= 16 (the group's query rows share one pass over its K/V);
+ * head q / q_group. G * q_group <= TF_MAX_QUERIES (the group's query rows share one pass over its K/V);
  * workspace queries then take G * q_group as their G. Other calls ignore q_group. */
 typedef struct tf_kv_desc {
     int32_t batch;
@@ -177,7 +177,7 @@ int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv
  * speculated rows, row len[b]-G+j iff bit j of tail_mask[g] is set (normally its ancestors and
  * itself). tail_mask[g] = (2 << g) - 1 reproduces causal != 0, 0xff reproduces causal == 0.
  *   tail_mask  in  HOST array of G bytes, read during the call (the only host-side input);
- *                  bits >= G are ignored.
+ *                  bits >= G are ignored. G <= 8 here (a mask row is one byte).
  * Other arguments, outputs, limits, workspace size and errors as tf_decode_attn_full
  * (tf_decode_attn_full_workspace_bytes); requires kv_len_all >= G. A query that sees nothing
  * gets O = 0, LSE = -inf.

@@ -15,7 +15,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtriforce_hip.so")
 
 TF_OK = 0
-TF_MAX_QUERIES = 8
+TF_MAX_QUERIES = 16
 TF_MAX_K_CHUNKS = 2048
 TF_MAX_SPEC = 16
 

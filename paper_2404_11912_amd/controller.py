@@ -117,3 +117,51 @@ class TriForceController:
             if self.on_update is not None:
                 self.on_update(emitted, rebuild)
         return tokens
+
+
+class TriForceModelLoop(TriForceController):
+    """Algorithm 1 for models whose next-token distribution depends on the tokens fed so far (real
+    forward passes with KV caches), where the position-indexed callbacks above do not suffice.
+    `spec` always denotes the tokens speculated in the current outer iteration, after the committed
+    sequence the model object keeps itself.
+
+    draft_fn(spec)            -> fp32 logits [V]: M_q's distribution of the token after committed + spec
+    retrieval_fn(spec, new)   -> fp32 logits [len(new)+1, V]: M_p over the retrieval cache, for the
+                                 positions after committed + spec + new[:i], i = 0 .. len(new)
+    target_fn(spec)           -> fp32 logits [len(spec)+1, V]: M_p over the full cache
+    on_update(tokens, rebuild)   the verified tokens to append to the committed sequence
+    """
+
+    def generate(self, n_tokens: int):
+        tokens, N = [], 0
+        while N < n_tokens:
+            x_hat, p_hat_rows = [], []
+            while len(x_hat) < self.g2:                          # first level
+                x_tilde, q_rows = [], []
+                for _ in range(self.g1):                         # M_q drafts token by token
+                    q = self.draft_fn(x_hat + x_tilde)
+                    q_rows.append(q)
+                    x_tilde.append(int(self._sample_rows(q[None], self._u(1))[0].item()))
+                q = torch.stack(q_rows)
+                p_hat = self.retrieval_fn(list(x_hat), list(x_tilde))
+                xt = torch.tensor(x_tilde, dtype=torch.int32, device=self.dev)
+                n1, emitted = self._accept(p_hat, q, xt, self._u(self.g1), self._u(1))
+                x_hat += emitted
+                p_hat_rows.append(p_hat[:n1 + 1])                # the rows that fixed these tokens
+                self.stats["inner_steps"] += 1
+                self.stats["drafted_l1"] += self.g1
+                self.stats["accepted_l1"] += n1
+            n = len(x_hat)
+            p = self.target_fn(list(x_hat))                      # second level
+            xs = torch.tensor(x_hat, dtype=torch.int32, device=self.dev)
+            n2, emitted = self._accept(p, torch.cat(p_hat_rows), xs, self._u(n), self._u(1))
+            tokens += emitted
+            N += n2 + 1
+            self.stats["outer_steps"] += 1
+            self.stats["drafted_l2"] += n
+            self.stats["accepted_l2"] += n2
+            rebuild = self.policy.update(n2, n)
+            self.stats["rebuilds"] += int(rebuild)
+            if self.on_update is not None:
+                self.on_update(emitted, rebuild)
+        return tokens

@@ -1,5 +1,5 @@
 // tf_decode_attn_full / tf_decode_attn_retrieval / tf_decode_attn_indexed / tf_decode_attn_tree:
-// attention of G <= 8 speculated query tokens over a long bf16 KV cache (Algorithm 1: the
+// attention of G <= 16 speculated query tokens over a long bf16 KV cache (Algorithm 1: the
 // M_p(C_p, ...) verification pass and the M_p(C_r, ...) drafting pass; the indexed form reads the
 // draft cache through the chunk indices of Sec. 4.1 instead of a gathered copy; the tree form
 // replaces the causal triangle over the G tokens by an ancestor mask, Sec. 5.3.3).
@@ -47,10 +47,10 @@ struct AttnParams {
     // r % Gm of query head r / Gm of the group; Gm = speculated tokens.
     int32_t H, G, Gm;
     // masked != 0: the last G tokens of the sequence are the queries' own; query g sees the
-    // tokens before them and the j-th of them iff bit j of byte g of tail_mask is set (causal:
+    // tokens before them and the j-th of them iff bit j of row g of tail_mask is set (causal:
     // bits 0..g; a token tree: the node's ancestors and itself). masked == 0: every query sees all.
     int32_t masked;
-    uint64_t tail_mask;
+    uint64_t tail_mask[4];  // 16 rows of 16 bits
     int32_t nsplit, tokens_per_split;
     float scale_log2;
     float *part_o;   // [BH][nsplit][rows][head dim], rows = 8 or 16 (the kernel's kRows)
@@ -134,7 +134,10 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     // tokens < n_all are visible to every query; of the last G tokens this lane's query sees
     // those whose bit is set in my_mask
     const int n_all = p.masked ? len - p.Gm : len;
-    const uint32_t my_mask = (uint32_t)(p.tail_mask >> (8 * (r % p.Gm))) & 0xffu;  // this lane's query
+    const int my_row = r % p.Gm;  // this lane's query token
+    const uint64_t my_word = my_row < 8 ? (my_row < 4 ? p.tail_mask[0] : p.tail_mask[1])
+                                        : (my_row < 12 ? p.tail_mask[2] : p.tail_mask[3]);
+    const uint32_t my_mask = (uint32_t)(my_word >> (16 * (my_row & 3))) & 0xffffu;
 
     f32x4_t o[kNE];
 #pragma unroll
@@ -540,7 +543,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     int rc = check_desc(kd, true);
     if (rc != TF_OK) return rc;
     if (G < 1 || kd->q_group < 0) return TF_ERR_INVALID_ARG;
-    if (G > TF_MAX_QUERIES) return TF_ERR_UNSUPPORTED;
+    if (G > TF_MAX_QUERIES || (tail_mask && G > 8)) return TF_ERR_UNSUPPORTED;  // tree masks are bytes
     const int q_group = kd->q_group > 0 ? kd->q_group : 1;  // query heads per KV head
     if ((int64_t)G * q_group > 16) return TF_ERR_UNSUPPORTED; // the rows are the 16 columns of one MFMA
     const int GQ = G * q_group;
@@ -577,10 +580,10 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.G = GQ;
     p.Gm = G;
     p.masked = (causal || tail_mask) ? 1 : 0;
-    p.tail_mask = 0;
+    for (int i = 0; i < 4; ++i) p.tail_mask[i] = 0;
     for (int g = 0; g < G; ++g) {
         const uint32_t row = tail_mask ? (tail_mask[g] & ((1u << G) - 1u)) : ((2u << g) - 1u);
-        p.tail_mask |= (uint64_t)row << (8 * g);
+        p.tail_mask[g >> 2] |= (uint64_t)row << (16 * (g & 3));
     }
     p.nsplit = sp.nsplit;
     p.tokens_per_split = sp.tokens_per_split;

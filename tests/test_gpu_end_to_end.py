@@ -1,0 +1,65 @@
+"""End to end: Algorithm 1 (both speculation levels, cache updates, retrieval rebuilds) driving a toy
+attention language model whose every attention, cache write, chunk summary, chunk selection and
+accept step runs through the C-ABI calls. The method's claim is that the output is that of the
+target model (Sec. 4.2): at temperature 0 the generated tokens must equal plain autoregressive
+greedy decoding of the target model, which the fp64 oracle computes on the CPU."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2404_11912_amd as tf
+from paper_2404_11912_amd.controller import RebuildPolicy, TriForceModelLoop
+from tests.toy_lm import ToyLM
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("g1,g2,stride,seed", [(2, 6, 3, 1), (1, 3, 1, 2), (3, 4, 0, 3)])
+def test_hierarchical_speculation_is_lossless_at_temperature_zero(g1, g2, stride, seed):
+    say(f"case end-to-end g1={g1} g2={g2} stride={stride} seed={seed}")
+    vocab, heads, n_prompt, n_new = 256, 2, 1500, 48
+    lm = ToyLM(vocab, heads, capacity=2048, chunk=8, k_chunks=16, window=48, seed=100 + seed)
+    g = torch.Generator().manual_seed(200 + seed)
+    prompt = torch.randint(0, vocab, (n_prompt,), generator=g).tolist()
+    want, gaps = lm.reference_greedy(prompt, n_new)
+    assert min(gaps) > 1e-4, "seed gives a near-tie in the target arg-max; pick another"
+    lm.prefill(prompt)
+    rng = np.random.default_rng(seed)
+    loop = TriForceModelLoop(lm.draft_step, lm.retrieval_pass, lm.target_pass,
+                             lambda n: rng.random(n, dtype=np.float32), vocab, gamma1=g1, gamma2=g2, temperature=0.0,
+                             policy=RebuildPolicy(stride=stride), on_update=lm.commit)
+    got = loop.generate(n_new)
+    st = loop.stats
+    say(f"[end-to-end] {len(got)} tokens in {st['outer_steps']} verification steps "
+        f"({len(got) / st['outer_steps']:.2f} tokens per step), level-1 acceptance "
+        f"{st['accepted_l1']}/{st['drafted_l1']}, level-2 acceptance {st['accepted_l2']}/{st['drafted_l2']}, "
+        f"{st['rebuilds']} rebuilds; smallest arg-max gap of the reference {min(gaps):.2e}")
+    assert got[:n_new] == want
+    assert lm.committed == prompt + got
+    if stride:
+        assert st["rebuilds"] >= 1
+
+
+def test_sampling_mode_runs_and_counts_are_consistent():
+    """Temperature 0.8: no token-by-token reference exists for a stochastic run; the loop's
+    bookkeeping must be consistent and every emitted token valid."""
+    say("case end-to-end sampling")
+    vocab = 256
+    lm = ToyLM(vocab, 2, capacity=1024, chunk=8, k_chunks=8, window=32, seed=321)
+    g = torch.Generator().manual_seed(322)
+    prompt = torch.randint(0, vocab, (600,), generator=g).tolist()
+    lm.prefill(prompt)
+    rng = np.random.default_rng(9)
+    loop = TriForceModelLoop(lm.draft_step, lm.retrieval_pass, lm.target_pass,
+                             lambda n: rng.random(n, dtype=np.float32), vocab, gamma1=2, gamma2=4, temperature=0.8,
+                             policy=RebuildPolicy(stride=2), on_update=lm.commit)
+    got = loop.generate(40)
+    st = loop.stats
+    assert all(0 <= t < vocab for t in got)
+    assert len(got) == st["accepted_l2"] + st["outer_steps"] and len(got) >= 40
+    assert st["accepted_l1"] <= st["drafted_l1"] and st["accepted_l2"] <= st["drafted_l2"]
+    assert lm.committed == prompt + got

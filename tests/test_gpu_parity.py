@@ -436,3 +436,14 @@ def test_attn_eight_queries_many_splits():
         check_attn(x, tf.tf_decode_attn_full, tag="G=8, 313 splits")
     finally:
         tf.tf_set_option("attn_full_tokens_per_split", 0)
+
+
+@pytest.mark.parametrize("G", [9, 12, 16])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attn_more_than_eight_queries(G, causal):
+    """Algorithm 1 verifies up to gamma1 + gamma2 + 1 tokens in one pass (9 at gamma1 = 2, gamma2 = 6);
+    up to 16 query rows fit the kernel's 16 MFMA columns."""
+    say(f"case attn G={G} causal={causal}")
+    x = synth.make_layer(B=2, H=3, N=2500, G=G, c=8, P=2, seed=9500 + G, device="cpu")
+    check_attn(x, tf.tf_decode_attn_full, kv_len=[2500, 333], kv_len_all=2500, causal=causal, tag=f"G={G}")
+    check_attn(x, tf.tf_decode_attn_retrieval, causal=causal, tag=f"G={G} retr")

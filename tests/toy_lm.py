@@ -1,0 +1,141 @@
+"""A toy one-layer attention language model for end-to-end tests of Algorithm 1 (test harness, not
+part of the library). Per-token query / key / value tables plus a position table, one multi-head
+attention layer over a KV cache, a linear read-out to logits. All attention, cache writes, chunk
+summaries and chunk selection run through the library's C-ABI calls on the GPU; the same model is
+also evaluated step by step on the CPU with the fp64 oracle (`reference_greedy`), from the same
+tables, so that the two share no arithmetic beyond elementwise table look-ups.
+
+Three tiers as in Algorithm 1, all sharing the weights and the full KV cache:
+  target     M_p over the full cache                    (tf_decode_attn_full)
+  retrieval  M_p over selected chunks + recent tokens   (tf_decode_attn_indexed, chunks from
+             tf_chunk_summarize + tf_chunk_topk_gather)
+  draft      a StreamingLLM-style cache: the first chunk (sinks) + a recent window
+             (tf_decode_attn_indexed)
+Invariant: the cache rows [0, len(committed) - 1) hold the committed tokens; the last committed
+token has not been fed yet. A pass feeds that token (or the last speculated one) plus new ones.
+"""
+import numpy as np
+import torch
+
+import paper_2404_11912_amd as tf
+
+D = 128
+
+
+class ToyLM:
+    def __init__(self, vocab, heads, capacity, chunk, k_chunks, window, seed, device="cuda"):
+        g = torch.Generator().manual_seed(seed)
+        self.V, self.H, self.cap, self.c, self.kc, self.win = vocab, heads, capacity, chunk, k_chunks, window
+        self.dev = torch.device(device)
+        r = lambda *shape: torch.randn(shape, generator=g)
+        self.Qtab = (r(vocab, heads, D) * 0.35).to(self.dev)
+        self.Ktab = r(vocab, heads, D).to(self.dev)
+        self.Vtab = r(vocab, heads, D).to(self.dev)
+        self.Ptab = (r(capacity, D) * 0.5).to(self.dev)               # position table, shared by the heads
+        self.Wo = (r(heads * D, vocab) * 0.5).to(self.dev)
+        self.K = torch.zeros((1, heads, capacity, D), dtype=torch.bfloat16, device=self.dev)
+        self.V_ = torch.zeros_like(self.K)
+        self.Kmean = torch.zeros((1, heads, capacity // chunk, D), dtype=torch.float32, device=self.dev)
+        self.idx = torch.full((1, heads, k_chunks), -1, dtype=torch.int32, device=self.dev)
+        self.sink = torch.zeros((1, heads, 1), dtype=torch.int32, device=self.dev)
+        self.committed, self.rb, self.summarized = [], 0, 0
+
+    # ---- elementwise look-ups (identical on CPU and GPU: one IEEE add, one rounding to bf16) ----
+    def qkv(self, tokens, pos0, tabs=None):
+        Qtab, Ktab, Vtab, Ptab = tabs or (self.Qtab, self.Ktab, self.Vtab, self.Ptab)
+        t = torch.as_tensor(tokens, dtype=torch.long, device=Qtab.device)
+        pos = Ptab[pos0:pos0 + len(tokens)][:, None, :]
+        q = (Qtab[t] + pos).to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()     # [1,H,n,D]
+        k = (Ktab[t] + pos).to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()
+        v = Vtab[t].to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()
+        return q, k, v
+
+    def _feed(self, tokens, pos0):
+        q, k, v = self.qkv(tokens, pos0)
+        tf.tf_kv_append(k, v, self.K, self.V_, pos_all=pos0)
+        return q
+
+    def _logits(self, O):                                              # [1,H,G,D] fp32 -> [G,V]
+        G = O.shape[2]
+        return (O[0].permute(1, 0, 2).reshape(G, self.H * D) @ self.Wo).contiguous()
+
+    # ---- the three tiers -------------------------------------------------------------------
+    def prefill(self, prompt):
+        self.committed = list(prompt)
+        self._feed(prompt[:-1], 0)
+        self.rebuild()
+
+    def rebuild(self):
+        """Summaries of the chunks completed by committed tokens, then chunk selection by the query of
+        the last committed token (Sec. 4.1); tokens behind the last complete chunk count as recent."""
+        n_rows = len(self.committed) - 1
+        n_chunks = n_rows // self.c
+        if n_chunks > self.summarized:
+            tf.tf_chunk_summarize(self.K, self.c, self.Kmean, self.summarized, n_chunks - self.summarized)
+            self.summarized = n_chunks
+        q, _, _ = self.qkv(self.committed[-1:], n_rows)
+        k = min(self.kc, n_chunks)
+        self.idx.fill_(-1)
+        if k > 0:
+            sel = torch.empty((1, self.H, k), dtype=torch.int32, device=self.dev)
+            tf.tf_chunk_topk_gather(q[:, :, 0].contiguous(), self.Kmean, self.K, self.V_, self.c, k, sel,
+                                    n_chunks_all=n_chunks)
+            self.idx[:, :, :k] = sel
+        self.rb = n_chunks * self.c
+
+    def target_pass(self, spec):
+        fed = [self.committed[-1]] + list(spec)
+        pos0 = len(self.committed) - 1
+        Q = self._feed(fed, pos0)
+        O = torch.empty(Q.shape, dtype=torch.float32, device=self.dev)
+        tf.tf_decode_attn_full(Q, self.K, self.V_, O, kv_len_all=pos0 + len(fed), scale=1.0, causal=True)
+        return self._logits(O)
+
+    def retrieval_pass(self, spec, new):
+        prev = spec[-1] if spec else self.committed[-1]
+        fed = [prev] + list(new)
+        pos0 = len(self.committed) - 1 + len(spec)
+        Q = self._feed(fed, pos0)
+        O = torch.empty(Q.shape, dtype=torch.float32, device=self.dev)
+        tf.tf_decode_attn_indexed(Q, self.K, self.V_, self.idx, self.c, O, kv_len_all=pos0 + len(fed),
+                                  recent_begin_all=self.rb, scale=1.0, causal=True)
+        return self._logits(O)
+
+    def draft_step(self, spec):
+        prev = spec[-1] if spec else self.committed[-1]
+        pos0 = len(self.committed) - 1 + len(spec)
+        Q = self._feed([prev], pos0)
+        O = torch.empty(Q.shape, dtype=torch.float32, device=self.dev)
+        length = pos0 + 1
+        tf.tf_decode_attn_indexed(Q, self.K, self.V_, self.sink, self.c, O, kv_len_all=length,
+                                  recent_begin_all=max(self.c, length - self.win), scale=1.0, causal=True)
+        return self._logits(O)[0].contiguous()
+
+    def commit(self, tokens, rebuild):
+        self.committed += list(tokens)
+        if rebuild:
+            self.rebuild()
+
+    # ---- plain autoregressive greedy decoding of the target model on the CPU (fp64 oracle) -----
+    def reference_greedy(self, prompt, n_new):
+        import oracle
+        from paper_2404_11912_amd import synth
+        tabs = tuple(t.cpu() for t in (self.Qtab, self.Ktab, self.Vtab, self.Ptab))
+        Wo = self.Wo.cpu().double().numpy()
+        toks = list(prompt)
+        _, k, v = self.qkv(toks, 0, tabs)
+        Kc, Vc = [synth.as_u16(k)], [synth.as_u16(v)]
+        gaps = []
+        for _ in range(n_new):
+            L = len(toks)
+            q, _, _ = self.qkv(toks[-1:], L - 1, tabs)
+            O, _, _ = oracle.attention(synth.as_u16(q), np.concatenate(Kc, axis=2), np.concatenate(Vc, axis=2),
+                                       scale=1.0, causal=False)
+            logits = O[0].transpose(1, 0, 2).reshape(1, self.H * D) @ Wo
+            order = np.argsort(-logits[0], kind="stable")
+            gaps.append(float(logits[0, order[0]] - logits[0, order[1]]))
+            toks.append(int(order[0]))
+            _, k, v = self.qkv(toks[-1:], L, tabs)
+            Kc.append(synth.as_u16(k))
+            Vc.append(synth.as_u16(v))
+        return toks[len(prompt):], gaps
