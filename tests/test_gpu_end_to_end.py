@@ -63,3 +63,38 @@ def test_sampling_mode_runs_and_counts_are_consistent():
     assert len(got) == st["accepted_l2"] + st["outer_steps"] and len(got) >= 40
     assert st["accepted_l1"] <= st["drafted_l1"] and st["accepted_l2"] <= st["drafted_l2"]
     assert lm.committed == prompt + got
+
+
+def test_first_generated_token_follows_the_target_distribution():
+    """Temperature 1: over many runs with fresh uniforms, the first token the hierarchy emits must be
+    distributed as the target model's next-token distribution (Sec. 4.2), whatever the two draft
+    tiers propose. Chi-square test on a 24-token vocabulary, 4000 runs, fixed seeds."""
+    from scipy.stats import chi2
+    say("case end-to-end first-token law")
+    vocab, runs = 24, 4000
+    lm = ToyLM(vocab, 2, capacity=512, chunk=8, k_chunks=4, window=16, seed=555)
+    g = torch.Generator().manual_seed(556)
+    prompt = torch.randint(0, vocab, (300,), generator=g).tolist()
+    lm.prefill(prompt)
+    lm.Wo *= 1.5 / float(lm.target_pass([])[0].std())       # a spread-out but not flat distribution
+    p = torch.softmax(lm.target_pass([])[0].double(), dim=0).cpu().numpy()
+    rng = np.random.default_rng(77)
+    counts = np.zeros(vocab)
+    acc1 = 0
+    for _ in range(runs):
+        lm.committed = list(prompt)                         # cache rows of the prompt stay valid
+        loop = TriForceModelLoop(lm.draft_step, lm.retrieval_pass, lm.target_pass,
+                                 lambda n: rng.random(n, dtype=np.float32), vocab, gamma1=2, gamma2=3, temperature=1.0,
+                                 on_update=lm.commit)
+        counts[loop.generate(1)[0]] += 1
+        acc1 += loop.stats["accepted_l2"] > 0
+    keep = p * runs >= 5                                     # cells with enough expected mass; the rest pooled
+    obs = np.append(counts[keep], counts[~keep].sum())
+    exp = np.append(p[keep], p[~keep].sum()) * runs
+    stat = float(((obs - exp) ** 2 / np.maximum(exp, 1e-12)).sum())
+    dof = len(obs) - 1
+    pval = float(chi2.sf(stat, dof))
+    say(f"[end-to-end law] chi2 = {stat:.1f} on {dof} dof, p = {pval:.3f}; first drafted token accepted in "
+        f"{acc1}/{runs} runs; largest target probability {p.max():.3f}")
+    assert pval > 1e-3
+    assert 0.05 * runs < acc1 < 0.999 * runs                 # the drafts are neither useless nor the target itself

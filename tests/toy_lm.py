@@ -28,10 +28,11 @@ class ToyLM:
         self.V, self.H, self.cap, self.c, self.kc, self.win = vocab, heads, capacity, chunk, k_chunks, window
         self.dev = torch.device(device)
         r = lambda *shape: torch.randn(shape, generator=g)
-        self.Qtab = (r(vocab, heads, D) * 0.35).to(self.dev)
+        self.Qtab = (r(vocab, heads, D) * 0.2).to(self.dev)
         self.Ktab = r(vocab, heads, D).to(self.dev)
         self.Vtab = r(vocab, heads, D).to(self.dev)
-        self.Ptab = (r(capacity, D) * 0.5).to(self.dev)               # position table, shared by the heads
+        self.Pq = (r(capacity, D) * 0.2).to(self.dev)                 # position tables (independent for queries
+        self.Pk = (r(capacity, D) * 0.5).to(self.dev)                 # and keys), shared by the heads
         self.Wo = (r(heads * D, vocab) * 0.5).to(self.dev)
         self.K = torch.zeros((1, heads, capacity, D), dtype=torch.bfloat16, device=self.dev)
         self.V_ = torch.zeros_like(self.K)
@@ -42,11 +43,12 @@ class ToyLM:
 
     # ---- elementwise look-ups (identical on CPU and GPU: one IEEE add, one rounding to bf16) ----
     def qkv(self, tokens, pos0, tabs=None):
-        Qtab, Ktab, Vtab, Ptab = tabs or (self.Qtab, self.Ktab, self.Vtab, self.Ptab)
+        Qtab, Ktab, Vtab, Pq, Pk = tabs or (self.Qtab, self.Ktab, self.Vtab, self.Pq, self.Pk)
         t = torch.as_tensor(tokens, dtype=torch.long, device=Qtab.device)
-        pos = Ptab[pos0:pos0 + len(tokens)][:, None, :]
-        q = (Qtab[t] + pos).to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()     # [1,H,n,D]
-        k = (Ktab[t] + pos).to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()
+        pq = Pq[pos0:pos0 + len(tokens)][:, None, :]
+        pk = Pk[pos0:pos0 + len(tokens)][:, None, :]
+        q = (Qtab[t] + pq).to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()      # [1,H,n,D]
+        k = (Ktab[t] + pk).to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()
         v = Vtab[t].to(torch.bfloat16).permute(1, 0, 2)[None].contiguous()
         return q, k, v
 
@@ -120,7 +122,7 @@ class ToyLM:
     def reference_greedy(self, prompt, n_new):
         import oracle
         from paper_2404_11912_amd import synth
-        tabs = tuple(t.cpu() for t in (self.Qtab, self.Ktab, self.Vtab, self.Ptab))
+        tabs = tuple(t.cpu() for t in (self.Qtab, self.Ktab, self.Vtab, self.Pq, self.Pk))
         Wo = self.Wo.cpu().double().numpy()
         toks = list(prompt)
         _, k, v = self.qkv(toks, 0, tabs)
