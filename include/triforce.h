@@ -259,6 +259,8 @@ int tf_kv_append(const void *Knew, const void *Vnew, int32_t n, void *K, void *V
  *                 drawn token, then -1.
  *   1 <= G <= TF_MAX_SPEC (G == 1: no drafted token, pointers to empty arrays may be NULL),
  *   V >= 1, temperature >= 0.
+ *   Logits of -inf (masked vocabulary entries) have probability 0; every row needs one finite
+ *   logit; +inf and NaN are not supported.
  * ------------------------------------------------------------------------------------- */
 size_t tf_spec_accept_workspace_bytes(int32_t B, int32_t G, int32_t V);
 int tf_spec_accept(const float *target_logits, const float *draft_logits,

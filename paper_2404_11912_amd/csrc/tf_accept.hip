@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_rowstats_kernel(const Acce
         }
     }
     double sum = 0.0;
-    if (p.T != 0.0) {
+    if (p.T != 0.0 && mx != -INFINITY) {  // a segment of masked (-inf) logits contributes nothing
         const double zmax = (double)mx / p.T;
 #pragma unroll
         for (int j = 0; j < kAccPer; ++j)
@@ -137,7 +137,8 @@ __device__ __forceinline__ RowStats combine_row(const AcceptParams &p, int b, in
     r.sum = 0.0;
     if (p.T != 0.0) {
         r.zmax = mx / p.T;
-        for (int s = 0; s < p.S; ++s) r.sum += st[s * 4 + 1] * exp(st[s * 4] / p.T - r.zmax);
+        for (int s = 0; s < p.S; ++s)
+            if (st[s * 4] != -INFINITY) r.sum += st[s * 4 + 1] * exp(st[s * 4] / p.T - r.zmax);
     }
     return r;
 }

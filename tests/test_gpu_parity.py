@@ -345,8 +345,13 @@ def test_whole_path_on_workload(name):
 
 
 # ----------------------------------------------------------------------------- accept
-def check_accept(B, gamma, V, T, seed, correlated):
+def check_accept(B, gamma, V, T, seed, correlated, mask=None):
     a = synth.make_accept_inputs(B, gamma, V, T, seed, correlated=correlated)
+    if mask is not None:                              # vocabulary entries masked out with -inf logits
+        a["target_logits"][..., mask] = -float("inf")
+        a["draft_logits"][..., mask] = -float("inf")
+        keep = torch.nonzero(~torch.as_tensor(mask)).flatten()
+        a["draft_tokens"] = keep[a["draft_tokens"].long() % keep.numel()].to(torch.int32)
     Tf = float(np.float32(T))                         # the C ABI takes the temperature as fp32
     n_o, out_o, ma, ms = oracle.accept(a["target_logits"].numpy(), a["draft_logits"].numpy(),
                                        a["draft_tokens"].numpy(), Tf, a["u_accept"].numpy(),
@@ -447,3 +452,17 @@ def test_attn_more_than_eight_queries(G, causal):
     x = synth.make_layer(B=2, H=3, N=2500, G=G, c=8, P=2, seed=9500 + G, device="cpu")
     check_attn(x, tf.tf_decode_attn_full, kv_len=[2500, 333], kv_len_all=2500, causal=causal, tag=f"G={G}")
     check_attn(x, tf.tf_decode_attn_retrieval, causal=causal, tag=f"G={G} retr")
+
+
+@pytest.mark.parametrize("T", [0.0, 0.7])
+def test_spec_accept_with_masked_vocabulary(T):
+    """-inf logits (masked or padded vocabulary entries), including a whole 4096-entry segment and
+    the tail of the vocabulary: such entries have probability 0 on both sides."""
+    say(f"case spec_accept masked vocabulary T={T}")
+    V = 14000
+    mask = np.zeros(V, dtype=bool)
+    mask[4096:8192] = True                            # one whole segment of the kernel
+    mask[13000:] = True                               # a padded tail
+    mask[np.random.default_rng(5).integers(0, 4096, 300)] = True
+    check_accept(16, 4, V, T, 9700, correlated=True, mask=mask)
+    check_accept(8, 3, V, T, 9701, correlated=False, mask=mask)

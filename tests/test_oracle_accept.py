@@ -189,3 +189,28 @@ def test_bad_token_raises():
     tl = np.zeros((1, 2, 4), np.float32); dl = np.zeros((1, 1, 4), np.float32)
     with pytest.raises(ValueError):
         oracle.accept(tl, dl, [[4]], 1.0, [[0.1]], [0.1])
+
+
+def test_masked_vocabulary_entries_equal_the_compacted_problem():
+    """-inf logits have probability 0: the result must be that of the problem with those entries
+    removed from the vocabulary (indices mapped back), and no masked token is ever emitted."""
+    rng = np.random.default_rng(61)
+    V, B, gamma = 40, 200, 3
+    mask = np.zeros(V, dtype=bool)
+    mask[rng.choice(V, 15, replace=False)] = True
+    keep = np.nonzero(~mask)[0]
+    t = (rng.standard_normal((B, gamma + 1, V)) * 2).astype(np.float32)
+    d = (t[:, :gamma] + rng.standard_normal((B, gamma, V)) * 0.7).astype(np.float32)
+    t[..., mask] = -np.inf
+    d[..., mask] = -np.inf
+    toks_c = rng.integers(0, keep.size, (B, gamma)).astype(np.int32)
+    ua = rng.random((B, gamma), dtype=np.float32)
+    us = rng.random(B, dtype=np.float32)
+    for T in (0.0, 0.8):
+        n1, o1, _, _ = oracle.accept(t, d, keep[toks_c].astype(np.int32), T, ua, us)
+        n2, o2, _, _ = oracle.accept(np.ascontiguousarray(t[..., keep]), np.ascontiguousarray(d[..., keep]), toks_c, T,
+                                     ua, us)
+        assert np.array_equal(n1, n2)
+        mapped = np.where(o2 >= 0, keep[np.maximum(o2, 0)], -1)
+        assert np.array_equal(o1, mapped)
+        assert not mask[o1[o1 >= 0]].any()
