@@ -72,8 +72,7 @@ int orc_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *V,
 {
     if (B <= 0 || H <= 0 || G <= 0 || N <= 0 || d <= 0) return -1;
     for (int b = 0; b < B; ++b) {
-        if (kv_len[b] < 1 || kv_len[b] > N) return -1;
-        if (causal && kv_len[b] < G) return -1;
+        if (kv_len[b] < 0 || kv_len[b] > N) return -1;
     }
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -82,11 +81,18 @@ int orc_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *V,
         int64_t n_all = kv_len[b];
         const uint16_t *Kbh = K + (int64_t)bh * N * d;
         const uint16_t *Vbh = V + (int64_t)bh * N * d;
-        double *z = (double *)malloc(sizeof(double) * (size_t)n_all);
+        double *z = (double *)malloc(sizeof(double) * (size_t)(n_all > 0 ? n_all : 1));
         if (!z) { failed = 1; continue; }
         for (int g = 0; g < G; ++g) {
             const uint16_t *q = Q + ((int64_t)bh * G + g) * d;
             int64_t n_g = causal ? (n_all - G + 1 + g) : n_all;
+            if (n_g <= 0) { /* a query that sees no key: O = 0, LSE = -inf by convention */
+                double *o0 = O + ((int64_t)bh * G + g) * d;
+                for (int j = 0; j < d; ++j) o0[j] = 0.0;
+                LSE[(int64_t)bh * G + g] = -INFINITY;
+                if (wsum) wsum[(int64_t)bh * G + g] = 0.0;
+                continue;
+            }
             double m = -INFINITY;
             for (int64_t t = 0; t < n_g; ++t) {
                 double acc = 0.0;

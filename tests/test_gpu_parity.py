@@ -466,3 +466,21 @@ def test_spec_accept_with_masked_vocabulary(T):
     mask[np.random.default_rng(5).integers(0, 4096, 300)] = True
     check_accept(16, 4, V, T, 9700, correlated=True, mask=mask)
     check_accept(8, 3, V, T, 9701, correlated=False, mask=mask)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_attn_empty_and_shorter_than_G_sequences(causal):
+    """Per-sequence lengths 0 and 2 < G in a batch: queries without a visible key return O = 0,
+    LSE = -inf; the others match the oracle."""
+    say(f"case attn short sequences causal={causal}")
+    x = synth.make_layer(B=4, H=2, N=700, G=5, c=8, P=2, seed=9800, device="cpu")
+    kv = [700, 0, 2, 5]
+    Qd, Kd, Vd = x["Q"].to(DEV), x["K"].to(DEV), x["V"].to(DEV)
+    for fn in (tf.tf_decode_attn_full, tf.tf_decode_attn_retrieval):
+        O, L = run_attn(fn, Qd, Kd, Vd, kv, 700, 1.0, causal)
+        Oo, Lo, _ = oracle.attention(synth.as_u16(x["Q"]), synth.as_u16(x["K"]), synth.as_u16(x["V"]), kv_len=kv,
+                                     scale=1.0, causal=causal)
+        assert np.array_equal(np.isneginf(L), np.isneginf(Lo))
+        fin = np.isfinite(Lo)
+        assert np.max(np.abs(O - Oo)) <= ATTN_TOL and np.max(np.abs(L[fin] - Lo[fin])) <= LSE_TOL
+        assert np.all(O[np.isneginf(Lo)] == 0.0)

@@ -170,7 +170,7 @@ def test_bad_arguments_raise():
     Q = np.zeros((1, 1, 4, D), np.uint16)
     K = np.zeros((1, 1, 8, D), np.uint16)
     with pytest.raises(ValueError):
-        oracle.attention(Q, K, K, kv_len=[2], causal=True)   # fewer tokens than queries
+        oracle.attention(Q, K, K, kv_len=[-1], causal=True)  # negative length
     with pytest.raises(ValueError):
         oracle.attention(Q, K, K, kv_len=[9], causal=False)  # beyond capacity
 
@@ -198,3 +198,33 @@ def test_grouped_query_oracle_reduces_to_per_head_attention():
     O1, L1 = oracle.attention_gqa(Q1, K, V, kv_len=kv, scale=0.8, causal=False)
     O2, L2, _ = oracle.attention(Q1, K, V, kv_len=kv, scale=0.8, causal=False)
     assert np.array_equal(O1, O2) and np.array_equal(L1, L2)
+
+
+def test_sequences_shorter_than_the_query_block_and_empty_sequences():
+    """kv_len < G with the causal mask, and kv_len = 0: query g sees max(0, kv_len - G + 1 + g) keys;
+    a query that sees none gets O = 0 and LSE = -inf (the library's documented convention). Pinned by
+    the scale-0 closed form and by the independently coded tree-mask path with the chain mask."""
+    rng = np.random.default_rng(91)
+    B, H, G, N = 4, 2, 5, 12
+    kv = np.array([12, 0, 2, 5], dtype=np.int32)
+    Q = _rand_u16(rng, (B, H, G, D), 0.3)
+    K = _rand_u16(rng, (B, H, N, D))
+    V = _rand_u16(rng, (B, H, N, D))
+    O, LSE, ws = oracle.attention(Q, K, V, kv_len=kv, scale=0.0, causal=True)
+    Vf = u16_f64(V)
+    for b in range(B):
+        for g in range(G):
+            n_g = max(0, int(kv[b]) - G + 1 + g)
+            if n_g == 0:
+                assert np.all(O[b, :, g] == 0.0) and np.all(np.isneginf(LSE[b, :, g])) and np.all(ws[b, :, g] == 0.0)
+            else:
+                assert np.max(np.abs(O[b, :, g] - Vf[b, :, :n_g].mean(axis=1))) < 1e-13
+                assert np.max(np.abs(LSE[b, :, g] - math.log(n_g))) < 1e-13
+    O1, L1, _ = oracle.attention(Q, K, V, kv_len=kv, scale=0.9, causal=True)
+    O2, L2 = oracle.attention_tree(Q, K, V, [(2 << g) - 1 for g in range(G)], kv_len=kv, scale=0.9)
+    assert np.max(np.abs(O1 - O2)) < 1e-13
+    assert np.array_equal(np.isneginf(L1), np.isneginf(L2))
+    fin = np.isfinite(L1)
+    assert np.max(np.abs(L1[fin] - L2[fin])) < 1e-13
+    O3, L3, _ = oracle.attention(Q, K, V, kv_len=np.array([3, 0, 0, 1], dtype=np.int32), scale=1.0, causal=False)
+    assert np.all(O3[1:3] == 0.0) and np.all(np.isneginf(L3[1:3])) and np.all(np.isfinite(L3[[0, 3]]))
