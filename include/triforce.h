@@ -58,7 +58,7 @@ extern "C" {
 #define TF_ERR_HIP (-4)         /* a HIP runtime call (kernel launch) reported an error      */
 
 #define TF_HEAD_DIM 128
-#define TF_MAX_QUERIES 16    /* G = gamma + 1 queries per attention call (8 with a tree mask) */
+#define TF_MAX_QUERIES 16    /* G = gamma + 1 queries (or tree nodes) per attention call      */
 #define TF_MAX_K_CHUNKS 2048 /* chunks kept by one tf_chunk_topk_gather call                 */
 #define TF_MAX_SPEC 16       /* G of tf_spec_accept                                          */
 
@@ -175,16 +175,16 @@ int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv
  * ancestor mask. The G speculated tokens are the last G rows of the cache, in any order that
  * puts parents before children; query g sees every row t < len[b]-G (the context) and, of the
  * speculated rows, row len[b]-G+j iff bit j of tail_mask[g] is set (normally its ancestors and
- * itself). tail_mask[g] = (2 << g) - 1 reproduces causal != 0, 0xff reproduces causal == 0.
- *   tail_mask  in  HOST array of G bytes, read during the call (the only host-side input);
- *                  bits >= G are ignored. G <= 8 here (a mask row is one byte).
+ * itself). tail_mask[g] = (2 << g) - 1 reproduces causal != 0, 0xffff reproduces causal == 0.
+ *   tail_mask  in  HOST array of G 16-bit rows, read during the call (the only host-side
+ *                  input); bits >= G are ignored.
  * Other arguments, outputs, limits, workspace size and errors as tf_decode_attn_full
  * (tf_decode_attn_full_workspace_bytes); requires kv_len_all >= G. A query that sees nothing
  * gets O = 0, LSE = -inf.
  * ------------------------------------------------------------------------------------- */
 int tf_decode_attn_tree(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
                         const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
-                        const uint8_t *tail_mask, float *O, float *LSE, void *ws, size_t ws_bytes,
+                        const uint16_t *tail_mask, float *O, float *LSE, void *ws, size_t ws_bytes,
                         void *stream);
 
 /* ---------------------------------------------------------------------------------------

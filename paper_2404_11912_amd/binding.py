@@ -86,7 +86,7 @@ def load_library() -> ctypes.CDLL:
     lib.tf_decode_attn_indexed.argtypes = [vp, vp, vp, dp, vp, i32, i32, vp, i64, vp, i64, i32, f32, i32, vp, vp,
                                            vp, sz, vp]
     lib.tf_decode_attn_tree.restype = ctypes.c_int
-    lib.tf_decode_attn_tree.argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, ctypes.POINTER(ctypes.c_uint8), vp, vp, vp,
+    lib.tf_decode_attn_tree.argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, ctypes.POINTER(ctypes.c_uint16), vp, vp, vp,
                                         sz, vp]
     lib.tf_kv_append.restype = ctypes.c_int
     lib.tf_kv_append.argtypes = [vp, vp, i32, vp, vp, dp, vp, i64, vp]
@@ -240,9 +240,9 @@ def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream, 
         ws = workspace(nbytes, K.device)
     if tail_mask is not None:
         rows = [int(m) for m in tail_mask]
-        if len(rows) != G or any(m < 0 or m > 255 for m in rows):
-            raise ValueError("tail_mask must hold G values in [0, 255]")
-        mask_arg = (ctypes.c_uint8 * G)(*rows)            # host array, read during the call
+        if len(rows) != G or any(m < 0 or m > 0xffff for m in rows):
+            raise ValueError("tail_mask must hold G values in [0, 65535]")
+        mask_arg = (ctypes.c_uint16 * G)(*rows)            # host array, read during the call
     else:
         mask_arg = int(bool(causal))
     _check(name, getattr(lib, name)(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(kv_len), int(kv_len_all),

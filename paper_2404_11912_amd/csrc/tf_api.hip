@@ -13,7 +13,7 @@ int topk_gather_launch(const void *, const void *, int64_t, const void *, const 
 size_t attn_workspace_bytes(int32_t, int32_t, int64_t, int32_t, bool);
 size_t attn_indexed_workspace_bytes(int32_t, int32_t, int32_t, int32_t, int64_t, int32_t);
 int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, const int32_t *, int64_t, int32_t,
-                float, int32_t, float *, float *, void *, size_t, void *, bool, const IndexedArgs *, const uint8_t *);
+                float, int32_t, float *, float *, void *, size_t, void *, bool, const IndexedArgs *, const uint16_t *);
 int kv_append_launch(const void *, const void *, int32_t, void *, void *, const tf_kv_desc *, const int32_t *,
                      int64_t, void *);
 int set_attn_option(bool retrieval, int64_t v);
@@ -87,7 +87,7 @@ int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv
 }
 
 int tf_decode_attn_tree(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
-                        int64_t kv_len_all, int32_t G, float scale, const uint8_t *tail_mask, float *O, float *LSE,
+                        int64_t kv_len_all, int32_t G, float scale, const uint16_t *tail_mask, float *O, float *LSE,
                         void *ws, size_t ws_bytes, void *stream) {
     if (!tail_mask) return TF_ERR_INVALID_ARG;
     return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, 0, O, LSE, ws, ws_bytes, stream, false, nullptr,

@@ -538,12 +538,12 @@ size_t attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chun
 
 int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
                 int64_t kv_len_all, int32_t G, float scale, int32_t causal, float *O, float *LSE, void *ws,
-                size_t ws_bytes, void *stream, bool retrieval, const IndexedArgs *ix, const uint8_t *tail_mask) {
+                size_t ws_bytes, void *stream, bool retrieval, const IndexedArgs *ix, const uint16_t *tail_mask) {
     if (!Q || !K || !V || !O) return TF_ERR_INVALID_ARG;
     int rc = check_desc(kd, true);
     if (rc != TF_OK) return rc;
     if (G < 1 || kd->q_group < 0) return TF_ERR_INVALID_ARG;
-    if (G > TF_MAX_QUERIES || (tail_mask && G > 8)) return TF_ERR_UNSUPPORTED;  // tree masks are bytes
+    if (G > TF_MAX_QUERIES) return TF_ERR_UNSUPPORTED;
     const int q_group = kd->q_group > 0 ? kd->q_group : 1;  // query heads per KV head
     if ((int64_t)G * q_group > 16) return TF_ERR_UNSUPPORTED; // the rows are the 16 columns of one MFMA
     const int GQ = G * q_group;

@@ -35,6 +35,7 @@ TREES = {
     "binary7": [-1, 0, 0, 1, 1, 2, 2],
     "two_chains6": [-1, 0, 1, -1, 3, 4],          # independent sequences sharing only the context
     "single": [-1],
+    "binary16": [-1, 0, 0, 1, 1, 2, 2, 3, 3, 4, 4, 5, 5, 6, 6, 7],
 }
 
 
@@ -64,7 +65,7 @@ def run(x, masks, kv_len=None, scale=1.0, tag=""):
 def test_tree_attention_vs_oracle(name, N):
     parent = TREES[name]
     say(f"case tree {name} N={N}")
-    x = synth.make_layer(B=2, H=3, N=N, G=8, c=8, P=4, seed=5300 + N + len(parent), device="cpu")
+    x = synth.make_layer(B=2, H=3, N=N, G=16, c=8, P=4, seed=5300 + N + len(parent), device="cpu")
     run(x, ancestor_masks(parent), tag=f"{name} N={N}")
 
 

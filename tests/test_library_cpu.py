@@ -94,14 +94,14 @@ def test_host_side_argument_checks(lib):
     assert lib.tf_chunk_summarize(None, ref(d), 8, 0, 8, p, 8, None) == -1
     assert lib.tf_spec_accept(None, p, p, 1, 2, 10, 1.0, p, p, p, p, p, 1 << 10, None) == -1
     assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 64, 4, 1.0, None, p, None, p, 1 << 20, None) == -1
-    m4 = (ctypes.c_uint8 * 4)(1, 3, 5, 9)
+    m4 = (ctypes.c_uint16 * 4)(1, 3, 5, 9)
     assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 3, 4, 1.0, m4, p, None, p, 1 << 20, None) == -1   # fewer rows than G
     assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 64, 4, 1.0, m4, p, None, p, 16, None) == -3
     # unsupported shapes
     assert lib.tf_decode_attn_full(p, p, p, ref(bad_dim), None, 64, 4, 1.0, 1, p, None, p, 1 << 20, None) == -2
     assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 64, 17, 1.0, 1, p, None, p, 1 << 20, None) == -2
-    m9 = (ctypes.c_uint8 * 9)(*([1] * 9))
-    assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 64, 9, 1.0, m9, p, None, p, 1 << 20, None) == -2
+    m17 = (ctypes.c_uint16 * 17)(*([1] * 17))
+    assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 64, 17, 1.0, m17, p, None, p, 1 << 20, None) == -2
     assert lib.tf_chunk_summarize(p, ref(d64), 8, 0, 8, p, 8, None) == -2
     assert lib.tf_decode_attn_full(p, p, p, ref(d64), None, 64, 4, 1.0, 1, p, None, p, 16, None) == -3   # accepted up to the workspace check
     assert lib.tf_chunk_topk_gather(p, p, 8, p, p, ref(d), 8, None, 8, 4096, p, None, None, None, None,
