@@ -22,6 +22,8 @@
  *   tf_decode_attn_tree       tf_decode_attn_full with a per-query mask over the speculated tokens
  * and a half-size variant of the average-key table:
  *   tf_chunk_summarize_bf16, tf_chunk_topk_gather_bf16
+ * and the accept step for batches with different draft lengths per sequence:
+ *   tf_spec_accept_ragged
  *
  * Conventions (all calls)
  *   - Every data pointer is a DEVICE pointer owned by the caller (the only host pointers are
@@ -268,6 +270,22 @@ int tf_spec_accept(const float *target_logits, const float *draft_logits,
                    float temperature, const float *u_accept, const float *u_sample,
                    int32_t *n_accepted, int32_t *out_tokens, void *ws, size_t ws_bytes,
                    void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_spec_accept_ragged -- tf_spec_accept for a batch whose sequences drafted different numbers
+ * of tokens (in Algorithm 1 the first level hands the verification between gamma2 and
+ * gamma1+gamma2 tokens, so the sequences of a batch differ).
+ *   n_draft  in  int32 [B] device array: sequence b drafted min(max(n_draft[b],0), G-1) tokens;
+ *                only its first n_draft[b] tokens / draft rows / uniforms and its first
+ *                n_draft[b]+1 target rows are used (arrays keep the strides of the G-wide call).
+ *   If all are accepted the bonus token is drawn from target row n_draft[b].
+ * Everything else as tf_spec_accept (same workspace size).
+ * ------------------------------------------------------------------------------------- */
+int tf_spec_accept_ragged(const float *target_logits, const float *draft_logits,
+                          const int32_t *draft_tokens, const int32_t *n_draft, int32_t B, int32_t G,
+                          int32_t V, float temperature, const float *u_accept,
+                          const float *u_sample, int32_t *n_accepted, int32_t *out_tokens, void *ws,
+                          size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -5,6 +5,7 @@ this package. It never imports the HIP package and shares no code with it.
 """
 from .tf_oracle import (  # noqa: F401
     accept,
+    accept_ragged,
     attention,
     attention_gqa,
     attention_indexed,

@@ -161,6 +161,28 @@ def accept(target_logits, draft_logits, draft_tokens, temperature: float, u_acce
     return n_acc, out, ma, ms
 
 
+def accept_ragged(target_logits, draft_logits, draft_tokens, n_draft, temperature: float, u_accept, u_sample):
+    """Accept step for a batch whose sequences drafted different numbers of tokens: sequence b is
+    the fixed-length problem with gamma = n_draft[b] on its leading rows (Algorithm 1 applied per
+    sequence). Same outputs as `accept`, out_tokens padded with -1 to the batch's G."""
+    tl = np.ascontiguousarray(target_logits, dtype=np.float32)
+    B, G, V = tl.shape
+    dl = np.asarray(draft_logits, dtype=np.float32).reshape(B, G - 1, V)
+    dt = np.asarray(draft_tokens, dtype=np.int32).reshape(B, G - 1)
+    ua = np.asarray(u_accept, dtype=np.float32).reshape(B, G - 1)
+    us = np.asarray(u_sample, dtype=np.float32).reshape(B)
+    n_acc = np.empty(B, dtype=np.int32)
+    out = np.full((B, G), -1, dtype=np.int32)
+    ma, ms = np.empty(B), np.empty(B)
+    for b in range(B):
+        g = int(min(max(int(n_draft[b]), 0), G - 1))
+        n, o, a, s = accept(tl[b:b + 1, :g + 1], dl[b:b + 1, :g], dt[b:b + 1, :g], temperature, ua[b:b + 1, :g],
+                            us[b:b + 1])
+        n_acc[b], ma[b], ms[b] = n[0], a[0], s[0]
+        out[b, :g + 1] = o[0]
+    return n_acc, out, ma, ms
+
+
 def attention_indexed(Q, K, V, idx, c: int, kv_len=None, recent_begin=None, scale: float = 1.0,
                       causal: bool = True, kv_len_all: int | None = None):
     """Gather-free drafting, written as its definition (Algorithm 1, M_p(C_r, ...); Sec. 4.1): for

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     tf_decode_attn_tree,
     tf_chunk_summarize_bf16,
     tf_chunk_topk_gather_bf16,
+    tf_spec_accept_ragged,
     tf_decode_attn_full_workspace_bytes,
     tf_decode_attn_retrieval,
     tf_decode_attn_retrieval_workspace_bytes,

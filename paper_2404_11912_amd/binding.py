@@ -29,6 +29,7 @@ EXPORTS = (
     "tf_decode_attn_indexed_workspace_bytes", "tf_decode_attn_indexed", "tf_kv_append",
     "tf_decode_attn_tree",
     "tf_chunk_summarize_bf16", "tf_chunk_topk_gather_bf16",
+    "tf_spec_accept_ragged",
 )
 
 
@@ -94,6 +95,8 @@ def load_library() -> ctypes.CDLL:
     lib.tf_spec_accept_workspace_bytes.argtypes = [i32, i32, i32]
     lib.tf_spec_accept.restype = ctypes.c_int
     lib.tf_spec_accept.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.tf_spec_accept_ragged.restype = ctypes.c_int
+    lib.tf_spec_accept_ragged.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -350,8 +353,15 @@ def tf_spec_accept_workspace_bytes(B: int, G: int, V: int) -> int:
     return int(load_library().tf_spec_accept_workspace_bytes(B, G, V))
 
 
+def tf_spec_accept_ragged(target_logits, draft_logits, draft_tokens, n_draft, temperature: float, u_accept,
+                          u_sample, n_accepted, out_tokens, ws=None, stream=None):
+    """tf_spec_accept with a per-sequence number of drafted tokens n_draft [B] (device int32)."""
+    return tf_spec_accept(target_logits, draft_logits, draft_tokens, temperature, u_accept, u_sample, n_accepted,
+                          out_tokens, ws, stream, n_draft=n_draft)
+
+
 def tf_spec_accept(target_logits, draft_logits, draft_tokens, temperature: float, u_accept, u_sample,
-                   n_accepted, out_tokens, ws=None, stream=None):
+                   n_accepted, out_tokens, ws=None, stream=None, n_draft=None):
     """Verify / Correct / bonus token for B sequences: fills n_accepted [B] and out_tokens [B,G]."""
     lib = load_library()
     _need(target_logits, torch.float32, "target_logits")
@@ -370,6 +380,17 @@ def tf_spec_accept(target_logits, draft_logits, draft_tokens, temperature: float
         raise ValueError("u_sample / n_accepted must be [B], out_tokens [B,G]")
     if ws is None:
         ws = workspace(tf_spec_accept_workspace_bytes(B, G, V), target_logits.device)
+    if n_draft is not None:
+        _need(n_draft, torch.int32, "n_draft")
+        if tuple(n_draft.shape) != (B,):
+            raise ValueError("n_draft must be [B]")
+        _check("tf_spec_accept_ragged",
+               lib.tf_spec_accept_ragged(_ptr(target_logits), _ptr(draft_logits) if G > 1 else None,
+                                         _ptr(draft_tokens) if G > 1 else None, _ptr(n_draft), B, G, V,
+                                         float(temperature), _ptr(u_accept) if G > 1 else None, _ptr(u_sample),
+                                         _ptr(n_accepted), _ptr(out_tokens), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream(stream)))
+        return n_accepted, out_tokens
     _check("tf_spec_accept",
            lib.tf_spec_accept(_ptr(target_logits), _ptr(draft_logits) if G > 1 else None,
                               _ptr(draft_tokens) if G > 1 else None, B, G, V, float(temperature),

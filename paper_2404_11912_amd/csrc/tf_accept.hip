@@ -26,6 +26,7 @@ constexpr int kNone = 0x7fffffff;
 struct AcceptParams {
     const float *tl, *dl;
     const int32_t *toks;
+    const int32_t *n_draft;  // [B] drafted tokens per sequence (<= G-1), or nullptr = G-1 for all
     int32_t B, G, V, S;  // S = segments per row
     double T;
     const float *ua, *us;
@@ -34,6 +35,11 @@ struct AcceptParams {
     double *part;       // [B][S][kAccThreads]: per-thread partial sums of the draw distribution
     double *seg_sum;    // [B][S]
 };
+
+// drafted tokens of sequence b (array strides stay G-1 whatever this count is)
+__device__ __forceinline__ int drafted(const AcceptParams &p, int b) {
+    return p.n_draft ? min(max(p.n_draft[b], 0), p.G - 1) : p.G - 1;
+}
 
 __device__ __forceinline__ const float *logits_row(const AcceptParams &p, int b, int rr) {
     return rr < p.G ? p.tl + ((int64_t)b * p.G + rr) * p.V
@@ -146,9 +152,9 @@ __device__ __forceinline__ RowStats combine_row(const AcceptParams &p, int b, in
 // Accept walk of sequence b by the first wave: lane i tests drafted position i, a ballot finds
 // the first rejection. Returns n (valid in every lane of the calling wave).
 __device__ __forceinline__ int accept_walk(const AcceptParams &p, int b, int lane) {
-    const int gamma = p.G - 1;
+    const int gamma = p.G - 1, mine = drafted(p, b);
     bool ok = true;
-    if (lane < gamma) {
+    if (lane < mine) {
         const int tok = p.toks[(int64_t)b * gamma + lane];
         ok = tok >= 0 && tok < p.V;
         if (ok) {
@@ -164,7 +170,7 @@ __device__ __forceinline__ int accept_walk(const AcceptParams &p, int b, int lan
         }
     }
     const unsigned long long rej = __builtin_amdgcn_ballot_w64(!ok);
-    return rej ? __builtin_ctzll(rej) : gamma;
+    return rej ? __builtin_ctzll(rej) : mine;
 }
 
 // mass of vocabulary entry with target logit t and draft logit dq in the distribution drawn from
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_mass_kernel(const AcceptPa
     }
     __syncthreads();
     const int n = s_n;
-    const bool rejected = n < gamma;
+    const bool rejected = n < drafted(p, b);
     const RowStats ts = combine_row(p, b, n);
     RowStats ds = ts;
     if (rejected) ds = combine_row(p, b, p.G + n);
@@ -245,7 +251,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const Accept
     }
     __syncthreads();
     const int n = s_n;
-    const bool rejected = n < gamma;
+    const bool rejected = n < drafted(p, b);
     const RowStats ts = combine_row(p, b, n);
 
     if (p.T == 0.0) {
@@ -376,7 +382,8 @@ size_t accept_workspace_bytes(int32_t B, int32_t G, int32_t V) {
 
 int accept_launch(const float *target_logits, const float *draft_logits, const int32_t *draft_tokens, int32_t B,
                   int32_t G, int32_t V, float temperature, const float *u_accept, const float *u_sample,
-                  int32_t *n_accepted, int32_t *out_tokens, void *ws, size_t ws_bytes, void *stream) {
+                  int32_t *n_accepted, int32_t *out_tokens, void *ws, size_t ws_bytes, void *stream,
+                  const int32_t *n_draft) {
     if (B < 1 || G < 1 || V < 1) return TF_ERR_INVALID_ARG;
     if (G > TF_MAX_SPEC) return TF_ERR_UNSUPPORTED;
     if (!target_logits || !u_sample || !n_accepted || !out_tokens) return TF_ERR_INVALID_ARG;
@@ -389,6 +396,7 @@ int accept_launch(const float *target_logits, const float *draft_logits, const i
     p.tl = target_logits;
     p.dl = draft_logits;
     p.toks = draft_tokens;
+    p.n_draft = n_draft;
     p.B = B;
     p.G = G;
     p.V = V;

@@ -20,7 +20,7 @@ int set_attn_option(bool retrieval, int64_t v);
 int set_score_option(int64_t v);
 size_t accept_workspace_bytes(int32_t, int32_t, int32_t);
 int accept_launch(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, float, const float *,
-                  const float *, int32_t *, int32_t *, void *, size_t, void *);
+                  const float *, int32_t *, int32_t *, void *, size_t, void *, const int32_t *);
 }  // namespace tf
 
 extern "C" {
@@ -131,7 +131,16 @@ int tf_spec_accept(const float *target_logits, const float *draft_logits, const 
                    int32_t G, int32_t V, float temperature, const float *u_accept, const float *u_sample,
                    int32_t *n_accepted, int32_t *out_tokens, void *ws, size_t ws_bytes, void *stream) {
     return tf::accept_launch(target_logits, draft_logits, draft_tokens, B, G, V, temperature, u_accept, u_sample,
-                             n_accepted, out_tokens, ws, ws_bytes, stream);
+                             n_accepted, out_tokens, ws, ws_bytes, stream, nullptr);
+}
+
+int tf_spec_accept_ragged(const float *target_logits, const float *draft_logits, const int32_t *draft_tokens,
+                          const int32_t *n_draft, int32_t B, int32_t G, int32_t V, float temperature,
+                          const float *u_accept, const float *u_sample, int32_t *n_accepted, int32_t *out_tokens,
+                          void *ws, size_t ws_bytes, void *stream) {
+    if (!n_draft) return TF_ERR_INVALID_ARG;
+    return tf::accept_launch(target_logits, draft_logits, draft_tokens, B, G, V, temperature, u_accept, u_sample,
+                             n_accepted, out_tokens, ws, ws_bytes, stream, n_draft);
 }
 
 }  // extern "C"

@@ -484,3 +484,26 @@ def test_attn_empty_and_shorter_than_G_sequences(causal):
         fin = np.isfinite(Lo)
         assert np.max(np.abs(O - Oo)) <= ATTN_TOL and np.max(np.abs(L[fin] - Lo[fin])) <= LSE_TOL
         assert np.all(O[np.isneginf(Lo)] == 0.0)
+
+
+@pytest.mark.parametrize("T", [0.0, 0.6])
+def test_spec_accept_ragged(T):
+    """Per-sequence numbers of drafted tokens (as after the first level of Algorithm 1), vocabulary
+    32000, against the oracle's per-sequence reduction."""
+    say(f"case spec_accept ragged T={T}")
+    B, gamma, V = 12, 8, 32000
+    a = synth.make_accept_inputs(B, gamma, V, T, 9900, correlated=True)
+    nd = np.array([8, 0, 3, 8, 6, 1, 7, 2, 8, 5, 4, 0], dtype=np.int32)
+    Tf = float(np.float32(T))
+    n_o, out_o, ma, ms = oracle.accept_ragged(a["target_logits"].numpy(), a["draft_logits"].numpy(),
+                                              a["draft_tokens"].numpy(), nd, Tf, a["u_accept"].numpy(),
+                                              a["u_sample"].numpy())
+    n = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    out = torch.full((B, gamma + 1), -9, dtype=torch.int32, device=DEV)
+    tf.tf_spec_accept_ragged(a["target_logits"].to(DEV), a["draft_logits"].to(DEV), a["draft_tokens"].to(DEV),
+                             torch.tensor(nd, device=DEV), T, a["u_accept"].to(DEV), a["u_sample"].to(DEV), n, out)
+    torch.cuda.synchronize()
+    safe = (ma > 1e-9) & (ms > 1e-9)
+    assert safe.all()
+    assert np.array_equal(n.cpu().numpy(), n_o) and np.array_equal(out.cpu().numpy(), out_o)
+    assert np.all(n_o <= nd)

@@ -97,6 +97,7 @@ def test_host_side_argument_checks(lib):
     m4 = (ctypes.c_uint16 * 4)(1, 3, 5, 9)
     assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 3, 4, 1.0, m4, p, None, p, 1 << 20, None) == -1   # fewer rows than G
     assert lib.tf_decode_attn_tree(p, p, p, ref(d), None, 64, 4, 1.0, m4, p, None, p, 16, None) == -3
+    assert lib.tf_spec_accept_ragged(p, p, p, None, 1, 2, 10, 1.0, p, p, p, p, p, 1 << 20, None) == -1
     # unsupported shapes
     assert lib.tf_decode_attn_full(p, p, p, ref(bad_dim), None, 64, 4, 1.0, 1, p, None, p, 1 << 20, None) == -2
     assert lib.tf_decode_attn_full(p, p, p, ref(d), None, 64, 17, 1.0, 1, p, None, p, 1 << 20, None) == -2

@@ -214,3 +214,35 @@ def test_masked_vocabulary_entries_equal_the_compacted_problem():
         mapped = np.where(o2 >= 0, keep[np.maximum(o2, 0)], -1)
         assert np.array_equal(o1, mapped)
         assert not mask[o1[o1 >= 0]].any()
+
+
+def test_ragged_accept_is_the_per_sequence_problem():
+    """n_draft = G-1 for every sequence reproduces the fixed-length call; a sequence with fewer drafted
+    tokens never looks past them: changing its unused trailing rows changes nothing, and with
+    n_draft = 0 the token is the inverse-CDF draw from target row 0."""
+    rng = np.random.default_rng(71)
+    B, G, V = 6, 5, 23
+    t = (rng.standard_normal((B, G, V)) * 2).astype(np.float32)
+    d = (t[:, :-1] + rng.standard_normal((B, G - 1, V)) * 0.5).astype(np.float32)
+    tok = rng.integers(0, V, (B, G - 1)).astype(np.int32)
+    ua = rng.random((B, G - 1), dtype=np.float32)
+    us = rng.random(B, dtype=np.float32)
+    full = oracle.accept(t, d, tok, 0.9, ua, us)
+    same = oracle.accept_ragged(t, d, tok, [G - 1] * B, 0.9, ua, us)
+    assert np.array_equal(full[0], same[0]) and np.array_equal(full[1], same[1])
+    nd = [0, 1, 2, 3, 4, 2]
+    r1 = oracle.accept_ragged(t, d, tok, nd, 0.9, ua, us)
+    t2, d2, tok2 = t.copy(), d.copy(), tok.copy()
+    for b, g in enumerate(nd):
+        t2[b, g + 1:] = 7.0
+        d2[b, g:] = -3.0
+        tok2[b, g:] = 0
+    r2 = oracle.accept_ragged(t2, d2, tok2, nd, 0.9, ua, us)
+    assert np.array_equal(r1[0], r2[0]) and np.array_equal(r1[1], r2[1])
+    assert np.all(r1[0] <= np.array(nd))
+    p0 = np.exp(t[0, 0].astype(np.float64) / np.float64(np.float32(0.9)))
+    cdf = np.cumsum(p0 / p0.sum())
+    assert r1[1][0, 0] == int(np.searchsorted(cdf, float(us[0]), side="right")) and r1[0][0] == 0
+    for b, g in enumerate(nd):                       # emitted: accepted tokens, one drawn token, then -1
+        n = r1[0][b]
+        assert np.array_equal(r1[1][b, :n], tok[b, :n]) and r1[1][b, n] >= 0 and np.all(r1[1][b, n + 1:] == -1)
