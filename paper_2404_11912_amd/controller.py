@@ -165,3 +165,84 @@ class TriForceModelLoop(TriForceController):
             if self.on_update is not None:
                 self.on_update(emitted, rebuild)
         return tokens
+
+
+class TriForceBatchLoop(TriForceController):
+    """Algorithm 1 for a batch of sequences advancing in lockstep (the batched setting of Sec. 5.1 /
+    Table 4). The first level repeats until every sequence holds at least gamma2 speculated tokens;
+    a sequence that already does sits the remaining inner iterations out (its slot still rides
+    through the calls, the results are ignored). The verification then sees a different number of
+    tokens per sequence, which `tf_spec_accept_ragged` handles; models pad the shorter sequences
+    BEHIND their real tokens, so the bottom-right causal mask keeps the padding invisible.
+
+    draft_fn(specs)          -> fp32 logits [B, V]   (specs: per sequence, the tokens speculated so far)
+    retrieval_fn(specs, new) -> fp32 logits [B, gamma1+1, V]
+    target_fn(specs)         -> fp32 logits [B, max_b len(specs[b]) + 1, V], rows left-aligned
+    on_update(emitted, rebuild): per-sequence lists of verified tokens, one rebuild flag for the batch
+    """
+
+    def __init__(self, batch: int, *args, **kwargs):
+        super().__init__(*args, **kwargs)
+        self.B = batch
+        self.ws = tf.workspace(tf.tf_spec_accept_workspace_bytes(batch, tf.TF_MAX_SPEC, self.V), self.dev)
+
+    def _accept_batch(self, target_logits, draft_logits, draft_tokens, n_draft=None):
+        B, G = target_logits.shape[:2]
+        n = torch.empty((B,), dtype=torch.int32, device=self.dev)
+        out = torch.empty((B, G), dtype=torch.int32, device=self.dev)
+        ua = self._u(B * (G - 1)).view(B, G - 1)
+        us = self._u(B)
+        if n_draft is None:
+            tf.tf_spec_accept(target_logits, draft_logits, draft_tokens, self.T, ua, us, n, out, ws=self.ws)
+        else:
+            tf.tf_spec_accept_ragged(target_logits, draft_logits, draft_tokens, n_draft, self.T, ua, us, n, out,
+                                     ws=self.ws)
+        return n.tolist(), out.tolist()
+
+    def generate(self, n_tokens: int):
+        B = self.B
+        tokens = [[] for _ in range(B)]
+        while min(len(t) for t in tokens) < n_tokens:
+            x_hat = [[] for _ in range(B)]
+            rows = [[] for _ in range(B)]
+            while min(len(x) for x in x_hat) < self.g2:          # first level
+                active = [len(x) < self.g2 for x in x_hat]
+                x_tilde = [[] for _ in range(B)]
+                q_rows = []
+                for _ in range(self.g1):
+                    q = self.draft_fn([x_hat[b] + x_tilde[b] for b in range(B)])
+                    q_rows.append(q)
+                    drawn = self._sample_rows(q, self._u(B)).tolist()
+                    for b in range(B):
+                        x_tilde[b].append(drawn[b])
+                q = torch.stack(q_rows, dim=1).contiguous()                  # [B, g1, V]
+                p_hat = self.retrieval_fn([list(x) for x in x_hat], [list(x) for x in x_tilde]).contiguous()
+                xt = torch.tensor(x_tilde, dtype=torch.int32, device=self.dev)
+                n1, out = self._accept_batch(p_hat, q, xt)
+                for b in range(B):
+                    if active[b]:
+                        x_hat[b] += out[b][:n1[b] + 1]
+                        rows[b].append(p_hat[b, :n1[b] + 1])
+                        self.stats["drafted_l1"] += self.g1
+                        self.stats["accepted_l1"] += n1[b]
+                self.stats["inner_steps"] += 1
+            n_b = [len(x) for x in x_hat]
+            Gm = max(n_b) + 1
+            p = self.target_fn([list(x) for x in x_hat]).contiguous()        # second level
+            d = torch.zeros((B, Gm - 1, self.V), dtype=torch.float32, device=self.dev)
+            xs = torch.zeros((B, Gm - 1), dtype=torch.int32, device=self.dev)
+            for b in range(B):
+                d[b, :n_b[b]] = torch.cat(rows[b])
+                xs[b, :n_b[b]] = torch.tensor(x_hat[b], dtype=torch.int32, device=self.dev)
+            n2, out = self._accept_batch(p, d, xs, torch.tensor(n_b, dtype=torch.int32, device=self.dev))
+            emitted = [out[b][:n2[b] + 1] for b in range(B)]
+            for b in range(B):
+                tokens[b] += emitted[b]
+            self.stats["outer_steps"] += 1
+            self.stats["drafted_l2"] += sum(n_b)
+            self.stats["accepted_l2"] += sum(n2)
+            rebuild = self.policy.update(sum(n2), sum(n_b))
+            self.stats["rebuilds"] += int(rebuild)
+            if self.on_update is not None:
+                self.on_update(emitted, rebuild)
+        return tokens

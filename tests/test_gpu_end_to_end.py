@@ -98,3 +98,34 @@ def test_first_generated_token_follows_the_target_distribution():
         f"{acc1}/{runs} runs; largest target probability {p.max():.3f}")
     assert pval > 1e-3
     assert 0.05 * runs < acc1 < 0.999 * runs                 # the drafts are neither useless nor the target itself
+
+
+def test_batched_hierarchical_speculation_is_lossless_at_temperature_zero():
+    """Three sequences of different prompt lengths advancing in lockstep (the batched setting of
+    Table 4): per-sequence cache lengths, per-sequence chunk counts and recent ranges, a different
+    number of speculated tokens per sequence at the verification (tf_spec_accept_ragged). Each
+    sequence must reproduce its own plain greedy decoding."""
+    from paper_2404_11912_amd.controller import TriForceBatchLoop
+    from tests.toy_lm import ToyLMBatch
+    say("case end-to-end batched")
+    vocab, heads, n_new, B = 256, 2, 32, 3
+    lm = ToyLMBatch(B, vocab, heads, capacity=1536, chunk=8, k_chunks=12, window=40, seed=777)
+    g = torch.Generator().manual_seed(778)
+    prompts = [torch.randint(0, vocab, (n,), generator=g).tolist() for n in (1200, 433, 900)]
+    wants = []
+    for p in prompts:
+        want, gaps = lm.reference_greedy(p, n_new)
+        assert min(gaps) > 1e-4, "seed gives a near-tie in the target arg-max; pick another"
+        wants.append(want)
+    lm.prefill(prompts)
+    rng = np.random.default_rng(4)
+    loop = TriForceBatchLoop(B, lm.draft_step, lm.retrieval_pass, lm.target_pass,
+                             lambda n: rng.random(n, dtype=np.float32), vocab, gamma1=2, gamma2=4, temperature=0.0,
+                             policy=RebuildPolicy(stride=3), on_update=lm.commit)
+    got = loop.generate(n_new)
+    st = loop.stats
+    say(f"[end-to-end batched] {[len(t) for t in got]} tokens in {st['outer_steps']} verification steps, level-2 "
+        f"acceptance {st['accepted_l2']}/{st['drafted_l2']}, {st['rebuilds']} rebuilds")
+    for b in range(B):
+        assert got[b][:n_new] == wants[b]
+        assert lm.committed[b] == prompts[b] + got[b]

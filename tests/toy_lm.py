@@ -141,3 +141,95 @@ class ToyLM:
             Kc.append(synth.as_u16(k))
             Vc.append(synth.as_u16(v))
         return toks[len(prompt):], gaps
+
+
+class ToyLMBatch(ToyLM):
+    """The same toy model for a batch of sequences of different lengths advancing in lockstep.
+    Rectangular calls: token lists are padded BEHIND the real tokens (token 0); the bottom-right
+    causal mask hides the padding from the real queries, whose outputs stay left-aligned."""
+
+    def __init__(self, batch, *args, **kwargs):
+        super().__init__(*args, **kwargs)
+        B = self.B = batch
+        self.K = torch.zeros((B, self.H, self.cap, D), dtype=torch.bfloat16, device=self.dev)
+        self.V_ = torch.zeros_like(self.K)
+        self.Kmean = torch.zeros((B, self.H, self.cap // self.c, D), dtype=torch.float32, device=self.dev)
+        self.idx = torch.full((B, self.H, self.kc), -1, dtype=torch.int32, device=self.dev)
+        self.sink = torch.zeros((B, self.H, 1), dtype=torch.int32, device=self.dev)
+        self.committed = [[] for _ in range(B)]
+        self.rb = torch.zeros((B,), dtype=torch.int32, device=self.dev)
+
+    def _i32(self, v):
+        return torch.tensor(v, dtype=torch.int32, device=self.dev)
+
+    def _feed_batch(self, fed, pos0):
+        """fed: per-sequence token lists, pos0: per-sequence first position. Returns Q [B,H,n,D]
+        (n = longest list) after writing the K/V rows of all (padded) tokens."""
+        n = max(len(f) for f in fed)
+        qs, ks, vs = [], [], []
+        for b in range(self.B):
+            q, k, v = self.qkv(list(fed[b]) + [0] * (n - len(fed[b])), pos0[b])
+            qs.append(q); ks.append(k); vs.append(v)
+        Q, Kn, Vn = torch.cat(qs), torch.cat(ks), torch.cat(vs)
+        tf.tf_kv_append(Kn, Vn, self.K, self.V_, pos=self._i32(pos0))
+        return Q, n
+
+    def prefill(self, prompts):
+        self.committed = [list(p) for p in prompts]
+        for b, p in enumerate(prompts):
+            _, k, v = self.qkv(p[:-1], 0)
+            self.K[b:b + 1, :, :len(p) - 1] = k
+            self.V_[b:b + 1, :, :len(p) - 1] = v
+        self.rebuild()
+
+    def rebuild(self):
+        n_rows = [len(c) - 1 for c in self.committed]
+        n_chunks = [r // self.c for r in n_rows]
+        top = max(n_chunks)
+        self.idx.fill_(-1)
+        if top > 0:
+            tf.tf_chunk_summarize(self.K, self.c, self.Kmean, 0, top)
+            q = torch.cat([self.qkv(self.committed[b][-1:], n_rows[b])[0] for b in range(self.B)])
+            k = min(self.kc, top)
+            sel = torch.empty((self.B, self.H, k), dtype=torch.int32, device=self.dev)
+            tf.tf_chunk_topk_gather(q[:, :, 0].contiguous(), self.Kmean, self.K, self.V_, self.c, k, sel,
+                                    n_chunks=self._i32(n_chunks), n_chunks_all=top)
+            self.idx[:, :, :k] = sel
+        self.rb = self._i32([n * self.c for n in n_chunks])
+
+    def target_pass(self, specs):
+        fed = [[self.committed[b][-1]] + list(specs[b]) for b in range(self.B)]
+        pos0 = [len(self.committed[b]) - 1 for b in range(self.B)]
+        Q, n = self._feed_batch(fed, pos0)
+        O = torch.empty(Q.shape, dtype=torch.float32, device=self.dev)
+        tf.tf_decode_attn_full(Q, self.K, self.V_, O, kv_len=self._i32([p + n for p in pos0]),
+                               kv_len_all=max(pos0) + n, scale=1.0, causal=True)
+        return torch.stack([self._logits(O[b:b + 1]) for b in range(self.B)])
+
+    def retrieval_pass(self, specs, news):
+        fed = [[specs[b][-1] if specs[b] else self.committed[b][-1]] + list(news[b]) for b in range(self.B)]
+        pos0 = [len(self.committed[b]) - 1 + len(specs[b]) for b in range(self.B)]
+        Q, n = self._feed_batch(fed, pos0)
+        O = torch.empty(Q.shape, dtype=torch.float32, device=self.dev)
+        tf.tf_decode_attn_indexed(Q, self.K, self.V_, self.idx, self.c, O, kv_len=self._i32([p + n for p in pos0]),
+                                  kv_len_all=max(pos0) + n, recent_begin=self.rb,
+                                  recent_begin_all=int(self.rb.min().item()), scale=1.0, causal=True)
+        return torch.stack([self._logits(O[b:b + 1]) for b in range(self.B)])
+
+    def draft_step(self, specs):
+        fed = [[specs[b][-1] if specs[b] else self.committed[b][-1]] for b in range(self.B)]
+        pos0 = [len(self.committed[b]) - 1 + len(specs[b]) for b in range(self.B)]
+        Q, _ = self._feed_batch(fed, pos0)
+        O = torch.empty(Q.shape, dtype=torch.float32, device=self.dev)
+        lens = [p + 1 for p in pos0]
+        rbs = [max(self.c, L - self.win) for L in lens]
+        tf.tf_decode_attn_indexed(Q, self.K, self.V_, self.sink, self.c, O, kv_len=self._i32(lens),
+                                  kv_len_all=max(lens), recent_begin=self._i32(rbs), recent_begin_all=min(rbs),
+                                  scale=1.0, causal=True)
+        return torch.stack([self._logits(O[b:b + 1])[0] for b in range(self.B)]).contiguous()
+
+    def commit(self, emitted, rebuild):
+        for b in range(self.B):
+            self.committed[b] += list(emitted[b])
+        if rebuild:
+            self.rebuild()
