@@ -48,7 +48,27 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     if verbose and out.strip():
         print(out)
     os.replace(tmp, LIB_PATH)
+    build_abi_check()
     return LIB_PATH
+
+
+ABI_CHECK = os.path.join(PKG, "abi_check")
+
+
+def build_abi_check() -> str:
+    """The plain-C client of the C ABI (csrc/abi_check.c), linked against the library just built."""
+    tmp = ABI_CHECK + f".{os.getpid()}.tmp"
+    # (the HIP runtime's C header wants its platform macro when included from a plain C file)
+    cmd = [hipcc(), "-x", "c", "-std=c99", "-O1", "-D__HIP_PLATFORM_AMD__", "-I", INCLUDE, "-I", "/opt/rocm/include",
+           os.path.join(CSRC, "abi_check.c"), "-x", "none", "-o", tmp, "-L", PKG, "-l:libtriforce_hip.so",
+           "-L", "/opt/rocm/lib", "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib"]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        if os.path.exists(tmp):
+            os.remove(tmp)
+        raise RuntimeError("building abi_check failed:\n" + res.stdout)
+    os.replace(tmp, ABI_CHECK)
+    return ABI_CHECK
 
 
 if __name__ == "__main__":

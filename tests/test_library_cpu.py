@@ -127,3 +127,16 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 16, 128, dtype=torch.bfloat16)
     with pytest.raises(TypeError):
         tf.kv_desc(x)
+
+
+def test_header_is_valid_c99_and_cxx():
+    """include/triforce.h must compile on its own as C99 and as C++ (no HIP or torch types in it)."""
+    import subprocess
+    import tempfile
+    inc = os.path.dirname(HEADER)
+    for lang, std in (("c", "-std=c99"), ("c++", "-std=c++11")):
+        with tempfile.NamedTemporaryFile("w", suffix=".c" if lang == "c" else ".cc") as f:
+            f.write('#include "triforce.h"\nint main(void) { tf_kv_desc d; d.q_group = 0; return d.q_group + TF_OK; }\n')
+            f.flush()
+            subprocess.check_call(["gcc" if lang == "c" else "g++", std, "-Wall", "-Werror", "-pedantic", "-fsyntax-only",
+                                   "-I", inc, f.name])
