@@ -39,13 +39,13 @@ def test_summarize_bf16(c):
     diff = got != want
     frac = float(diff.mean())
     say(f"[bf16 means c={c}] entries differing from the once-rounded exact mean: {frac:.2e}")
-    if c & (c - 1) == 0:
-        assert frac == 0.0                    # sums and the division are exact: one rounding on both sides
-    else:
-        # fp32 division rounds before the bf16 rounding: a rare one-ulp (2^-8 relative) difference
-        assert frac < 1e-3
-        if diff.any():
-            assert np.max(np.abs(got - want)[diff] / np.abs(want[diff])) <= 2.0 ** -7
+    # The device rounds twice (fp32 sum and division, then bf16); the oracle rounds the exact mean once.
+    # The two differ only when the fp32 result falls on the other side of a bf16 rounding boundary:
+    # rare (about one entry in 10^5 .. 10^6, less for power-of-two chunks whose division is exact),
+    # and then by one bf16 ulp.
+    assert frac < (1e-4 if c & (c - 1) == 0 else 1e-3)
+    if diff.any():
+        assert np.max(np.abs(got - want)[diff] / np.abs(want[diff])) <= 2.0 ** -7
 
 
 @pytest.mark.parametrize("N,c,k,P", [(4096, 8, 64, 8), (32768, 8, 512, 64), (8192, 16, 100, 16), (3000, 4, 37, 4)])
