@@ -2,8 +2,6 @@
 indexed, both head sizes, grouped heads, strided layouts, per-sequence lengths incl. 0, split-size
 options), retrieval (fp32 and bf16 tables, per-sequence chunk counts) and the accept step (fixed and
 ragged, vocabulary sizes around the kernel's 4096-entry segments), each case against the oracle."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -21,22 +19,32 @@ DEV = "cuda"
 def u16(t): return synth.as_u16(t.cpu())
 
 def attn_case(rng, i):
-    d = int(rng.choice([64, 128])); qg = int(rng.choice([1, 1, 2, 4])); G = int(rng.integers(1, 16 // qg + 1))
-    B = int(rng.integers(1, 4)); Hkv = int(rng.integers(1, 5)); N = int(rng.integers(max(G, 1), int(os.environ.get('NMAX', '6000'))))
-    causal = bool(rng.integers(0, 2)); tps = int(rng.choice([0, 0, 64, 128, 512, 2048]))
-    retr = bool(rng.integers(0, 2)); strided = bool(rng.integers(0, 3) == 0)
+    d = int(rng.choice([64, 128]))
+    qg = int(rng.choice([1, 1, 2, 4]))
+    G = int(rng.integers(1, 16 // qg + 1))
+    B = int(rng.integers(1, 4))
+    Hkv = int(rng.integers(1, 5))
+    N = int(rng.integers(max(G, 1), 6000))
+    causal = bool(rng.integers(0, 2))
+    tps = int(rng.choice([0, 0, 64, 128, 512, 2048]))
+    retr = bool(rng.integers(0, 2))
+    strided = bool(rng.integers(0, 3) == 0)
     scale = float(rng.choice([1.0, d ** -0.5, 0.0, 3.0]))
-    kv = [int(rng.integers(0, N + 1)) for _ in range(B)]; kv[int(rng.integers(0, B))] = N
+    kv = [int(rng.integers(0, N + 1)) for _ in range(B)]
+    kv[int(rng.integers(0, B))] = N
     desc = f"attn d={d} qg={qg} G={G} B={B} Hkv={Hkv} N={N} causal={causal} tps={tps} retr={retr} strided={strided} scale={scale:.3f} kv={kv}"
     print(f"[{i}] {desc}", flush=True)
     g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
     if strided:
-        Kb = torch.randn((B, N, Hkv, d), generator=g).to(torch.bfloat16).to(DEV); Vb = torch.randn((B, N, Hkv, d), generator=g).to(torch.bfloat16).to(DEV)
+        Kb = torch.randn((B, N, Hkv, d), generator=g).to(torch.bfloat16).to(DEV)
+        Vb = torch.randn((B, N, Hkv, d), generator=g).to(torch.bfloat16).to(DEV)
         K, V = Kb.permute(0, 2, 1, 3), Vb.permute(0, 2, 1, 3)
     else:
-        K = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16).to(DEV); V = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16).to(DEV)
+        K = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16).to(DEV)
+        V = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16).to(DEV)
     Q = (torch.randn((B, Hkv * qg, G, d), generator=g) * 0.3).to(torch.bfloat16).to(DEV)
-    O = torch.full(Q.shape, float("nan"), dtype=torch.float32, device=DEV); L = torch.full(Q.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    O = torch.full(Q.shape, float("nan"), dtype=torch.float32, device=DEV)
+    L = torch.full(Q.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
     opt = "attn_retr_tokens_per_split" if retr else "attn_full_tokens_per_split"
     tf.tf_set_option(opt, tps)
     try:
@@ -53,18 +61,26 @@ def attn_case(rng, i):
     assert e <= 2e-3 and el <= 1e-3, (e, el)
 
 def indexed_case(rng, i):
-    d = int(rng.choice([64, 128])); G = int(rng.integers(1, 9)); B = int(rng.integers(1, 4)); H = int(rng.integers(1, 5))
-    c = int(rng.integers(1, 33)); N = int(rng.integers(G + c, int(os.environ.get('NMAX', '5000')))); k = int(rng.integers(0, 30)); causal = bool(rng.integers(0, 2))
+    d = int(rng.choice([64, 128]))
+    G = int(rng.integers(1, 9))
+    B = int(rng.integers(1, 4))
+    H = int(rng.integers(1, 5))
+    c = int(rng.integers(1, 33))
+    N = int(rng.integers(G + c, 5000))
+    k = int(rng.integers(0, 30))
+    causal = bool(rng.integers(0, 2))
     kv = [int(rng.integers(G, N + 1)) for _ in range(B)]
     rbs = [int(rng.integers(0, kvb - G + 1)) for kvb in kv]
     M = N // c
     desc = f"indexed d={d} G={G} B={B} H={H} c={c} N={N} k={k} causal={causal} kv={kv} rb={rbs}"
     print(f"[{i}] {desc}", flush=True)
     g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
-    K = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV); V = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    K = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    V = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV)
     Q = (torch.randn((B, H, G, d), generator=g) * 0.3).to(torch.bfloat16).to(DEV)
     idx = torch.from_numpy(rng.integers(-1, max(M, 1), (B, H, max(k, 1))).astype(np.int32))[:, :, :k].contiguous()
-    O = torch.empty(Q.shape, dtype=torch.float32, device=DEV); L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+    O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+    L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
     tf.tf_decode_attn_indexed(Q, K, V, idx.to(DEV), c, O, L, kv_len=torch.tensor(kv, dtype=torch.int32, device=DEV), kv_len_all=N,
                               recent_begin=torch.tensor(rbs, dtype=torch.int32, device=DEV), recent_begin_all=min(rbs), causal=causal)
     torch.cuda.synchronize()
@@ -75,16 +91,23 @@ def indexed_case(rng, i):
     assert e <= 2e-3 and el <= 1e-3, (e, el)
 
 def topk_case(rng, i):
-    B = int(rng.integers(1, 4)); H = int(rng.integers(1, 5)); c = int(rng.integers(1, 33)); M = int(rng.integers(1, 3000))
-    N = M * c + int(rng.integers(0, c)); k = int(rng.integers(1, min(M, 300) + 1)); bf = bool(rng.integers(0, 2))
-    nc = [int(rng.integers(0, M + 1)) for _ in range(B)]; nc[int(rng.integers(0, B))] = M
+    B = int(rng.integers(1, 4))
+    H = int(rng.integers(1, 5))
+    c = int(rng.integers(1, 33))
+    M = int(rng.integers(1, 3000))
+    N = M * c + int(rng.integers(0, c))
+    k = int(rng.integers(1, min(M, 300) + 1))
+    bf = bool(rng.integers(0, 2))
+    nc = [int(rng.integers(0, M + 1)) for _ in range(B)]
+    nc[int(rng.integers(0, B))] = M
     print(f"[{i}] topk B={B} H={H} c={c} M={M} N={N} k={k} bf16={bf} nc={nc}", flush=True)
     x = synth.make_layer(B=B, H=H, N=N, G=2, c=c, P=min(4, M), seed=int(rng.integers(1 << 30)), device="cpu")
     K, V, q_r = x["K"].to(DEV), x["V"].to(DEV), x["q_r"].to(DEV)
     Kmean = torch.empty((B, H, M, 128), dtype=torch.bfloat16 if bf else torch.float32, device=DEV)
     (tf.tf_chunk_summarize_bf16 if bf else tf.tf_chunk_summarize)(K, c, Kmean)
     idx = torch.empty((B, H, k), dtype=torch.int32, device=DEV)
-    Kr = torch.zeros((B, H, k * c, 128), dtype=torch.bfloat16, device=DEV); Vr = torch.zeros_like(Kr)
+    Kr = torch.zeros((B, H, k * c, 128), dtype=torch.bfloat16, device=DEV)
+    Vr = torch.zeros_like(Kr)
     (tf.tf_chunk_topk_gather_bf16 if bf else tf.tf_chunk_topk_gather)(q_r, Kmean, K, V, c, k, idx, Kr, Vr, n_chunks=torch.tensor(nc, dtype=torch.int32, device=DEV), n_chunks_all=M)
     torch.cuda.synchronize()
     if bf:
@@ -113,19 +136,27 @@ def topk_case(rng, i):
             assert torch.equal(Vr[b, h, :keff * c].view(torch.int16), V[b, h, rows].view(torch.int16))
 
 def accept_case(rng, i):
-    B = int(rng.integers(1, 9)); gamma = int(rng.integers(0, 16)); V = int(rng.choice([2, 17, 1000, 4096, 4097, 9000, 33000]))
-    T = float(rng.choice([0.0, 0.3, 1.0, 1.7])); ragged = bool(rng.integers(0, 2)) and gamma > 0
+    B = int(rng.integers(1, 9))
+    gamma = int(rng.integers(0, 16))
+    V = int(rng.choice([2, 17, 1000, 4096, 4097, 9000, 33000]))
+    T = float(rng.choice([0.0, 0.3, 1.0, 1.7]))
+    ragged = bool(rng.integers(0, 2)) and gamma > 0
     print(f"[{i}] accept B={B} gamma={gamma} V={V} T={T} ragged={ragged}", flush=True)
     if gamma == 0:
-        t = torch.from_numpy((rng.standard_normal((B, 1, V)) * 2).astype(np.float32)); us = torch.from_numpy(rng.random(B, dtype=np.float32))
-        n = torch.empty((B,), dtype=torch.int32, device=DEV); out = torch.empty((B, 1), dtype=torch.int32, device=DEV)
-        tf.tf_spec_accept(t.to(DEV), None, None, T, None, us.to(DEV), n, out); torch.cuda.synchronize()
+        t = torch.from_numpy((rng.standard_normal((B, 1, V)) * 2).astype(np.float32))
+        us = torch.from_numpy(rng.random(B, dtype=np.float32))
+        n = torch.empty((B,), dtype=torch.int32, device=DEV)
+        out = torch.empty((B, 1), dtype=torch.int32, device=DEV)
+        tf.tf_spec_accept(t.to(DEV), None, None, T, None, us.to(DEV), n, out)
+        torch.cuda.synchronize()
         no, oo, ma, ms = oracle.accept(t.numpy(), np.zeros((B, 0, V), np.float32), np.zeros((B, 0), np.int32), float(np.float32(T)), np.zeros((B, 0), np.float32), us.numpy())
         safe = ms > 1e-9
-        assert np.array_equal(out.cpu().numpy()[safe], oo[safe]); return
+        assert np.array_equal(out.cpu().numpy()[safe], oo[safe])
+        return
     a = synth.make_accept_inputs(B, gamma, V, max(T, 0.5), int(rng.integers(1 << 30)), correlated=bool(rng.integers(0, 2)))
     nd = rng.integers(0, gamma + 1, B).astype(np.int32) if ragged else None
-    n = torch.empty((B,), dtype=torch.int32, device=DEV); out = torch.empty((B, gamma + 1), dtype=torch.int32, device=DEV)
+    n = torch.empty((B,), dtype=torch.int32, device=DEV)
+    out = torch.empty((B, gamma + 1), dtype=torch.int32, device=DEV)
     args = (a["target_logits"].to(DEV), a["draft_logits"].to(DEV), a["draft_tokens"].to(DEV))
     Tf = float(np.float32(T))
     if ragged:
