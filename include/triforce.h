@@ -236,6 +236,7 @@ int tf_decode_attn_indexed(const void *Q, const void *K, const void *V, const tf
  *   K, V       out bf16, described by kd; bit-exact row copies; other rows untouched
  *   pos        in  int32 [batch] device array, or NULL
  * Destination rows outside [0, capacity) are dropped (only possible with a device `pos`).
+ * n == 0 is a valid no-op (Knew and Vnew may then be NULL).
  * Appending to the full cache uses p = current length; committing accepted tokens to a
  * retrieval cache of budget R that already holds m committed tokens uses p = R - m - n (the
  * tail of the descending-importance order).

@@ -31,10 +31,11 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams p) {
 
 int kv_append_launch(const void *Knew, const void *Vnew, int32_t n, void *K, void *V, const tf_kv_desc *kd,
                      const int32_t *pos, int64_t pos_all, void *stream) {
-    if (!Knew || !Vnew || !K || !V) return TF_ERR_INVALID_ARG;
+    if (!K || !V) return TF_ERR_INVALID_ARG;
     int rc = check_desc(kd, true);
     if (rc != TF_OK) return rc;
     if (n < 0 || pos_all < 0) return TF_ERR_INVALID_ARG;
+    if (n > 0 && (!Knew || !Vnew)) return TF_ERR_INVALID_ARG;  // nothing is read when n == 0
     if (!pos && pos_all + n > kd->capacity) return TF_ERR_INVALID_ARG;
     if (pos_all > (int64_t)1 << 30 || n > (1 << 20)) return TF_ERR_UNSUPPORTED;
     if (!aligned(Knew, 16) || !aligned(Vnew, 16) || !aligned(K, 16) || !aligned(V, 16)) return TF_ERR_INVALID_ARG;

@@ -119,6 +119,10 @@ def test_kv_append_into_a_strided_cache_with_a_scalar_position():
     assert np.array_equal(synth.as_u16(Kd.contiguous()), Ko) and np.array_equal(synth.as_u16(Vd.contiguous()), Vo)
     with pytest.raises(tf.TfError):
         tf.tf_kv_append(new["K"].to(DEV), new["V"].to(DEV), Kd, Vd, pos_all=47)     # would run off the end
+    empty = torch.empty((B, H, 0, 128), dtype=torch.bfloat16, device=DEV)         # nothing accepted: a no-op
+    tf.tf_kv_append(empty, empty, Kd, Vd, pos_all=50)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.as_u16(Kd.contiguous()), Ko) and np.array_equal(synth.as_u16(Vd.contiguous()), Vo)
 
 
 def test_retrieval_cache_maintenance_scenario():

@@ -1,7 +1,9 @@
 """Seeded randomized sweep through the documented argument ranges of the attention calls (plain and
 indexed, both head sizes, grouped heads, strided layouts, per-sequence lengths incl. 0, split-size
 options), retrieval (fp32 and bf16 tables, per-sequence chunk counts) and the accept step (fixed and
-ragged, vocabulary sizes around the kernel's 4096-entry segments), each case against the oracle."""
+ragged, vocabulary sizes around the kernel's 4096-entry segments), tree-masked verification (random
+masks of up to 16 nodes) and the cache append (positions that run off either end), each case against
+the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -171,11 +173,64 @@ def accept_case(rng, i):
 
 
 
-CASES = [attn_case, indexed_case, topk_case, accept_case]
+def tree_case(rng, i):
+    d = int(rng.choice([64, 128]))
+    G = int(rng.integers(1, 17))
+    B = int(rng.integers(1, 4))
+    H = int(rng.integers(1, 4))
+    N = int(rng.integers(G, 5000))
+    kv = [int(rng.integers(G, N + 1)) for _ in range(B)]
+    masks = [int(rng.integers(0, 1 << G)) for _ in range(G)]        # arbitrary, rows may see nothing
+    print(f"[{i}] tree d={d} G={G} B={B} H={H} N={N} kv={kv} masks={masks}", flush=True)
+    g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+    K = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    V = torch.randn((B, H, N, d), generator=g).to(torch.bfloat16).to(DEV)
+    Q = (torch.randn((B, H, G, d), generator=g) * 0.3).to(torch.bfloat16).to(DEV)
+    O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+    L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_tree(Q, K, V, masks, O, L, kv_len=torch.tensor(kv, dtype=torch.int32, device=DEV), kv_len_all=N)
+    torch.cuda.synchronize()
+    Oo, Lo = oracle.attention_tree(u16(Q), u16(K), u16(V), masks, kv_len=kv)
+    Lg = L.cpu().numpy().astype(np.float64)
+    assert np.array_equal(np.isneginf(Lg), np.isneginf(Lo))
+    fin = np.isfinite(Lo)
+    assert float(np.max(np.abs(O.cpu().numpy() - Oo))) <= 2e-3
+    assert not fin.any() or float(np.max(np.abs(Lg[fin] - Lo[fin]))) <= 1e-3
+
+
+def append_case(rng, i):
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 5))
+    H = int(rng.integers(1, 5))
+    N = int(rng.integers(40, 600))
+    n = int(rng.integers(0, 40))
+    strided = bool(rng.integers(0, 2))
+    pos = rng.integers(-3, N + 3, B).astype(np.int32) if rng.integers(0, 2) else None   # may run off either end
+    pos_all = int(rng.integers(0, N - n + 1))
+    print(f"[{i}] append d={d} B={B} H={H} N={N} n={n} strided={strided} "
+          f"pos={None if pos is None else pos.tolist()} pos_all={pos_all}", flush=True)
+    g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+    shape = (B, N, H, d) if strided else (B, H, N, d)
+    Kb = torch.randn(shape, generator=g).to(torch.bfloat16)
+    Vb = torch.randn(shape, generator=g).to(torch.bfloat16)
+    Kn = torch.randn((B, H, n, d), generator=g).to(torch.bfloat16)
+    Vn = torch.randn((B, H, n, d), generator=g).to(torch.bfloat16)
+    Kd, Vd = Kb.to(DEV), Vb.to(DEV)
+    Kv, Vv = (Kd.permute(0, 2, 1, 3), Vd.permute(0, 2, 1, 3)) if strided else (Kd, Vd)
+    tf.tf_kv_append(Kn.to(DEV), Vn.to(DEV), Kv, Vv, pos=None if pos is None else torch.tensor(pos, device=DEV),
+                    pos_all=pos_all)
+    torch.cuda.synchronize()
+    Kh = Kb.permute(0, 2, 1, 3).contiguous() if strided else Kb
+    Vh = Vb.permute(0, 2, 1, 3).contiguous() if strided else Vb
+    Ko, Vo = oracle.kv_append(u16(Kn), u16(Vn), u16(Kh), u16(Vh), pos if pos is not None else pos_all)
+    assert np.array_equal(u16(Kv.contiguous()), Ko) and np.array_equal(u16(Vv.contiguous()), Vo)
+
+
+CASES = [attn_case, indexed_case, topk_case, accept_case, tree_case, append_case]
 
 
 @pytest.mark.parametrize("block", range(4))
 def test_random_sweep(block):
-    for i in range(block * 24, block * 24 + 24):
+    for i in range(block * 30, block * 30 + 30):
         rng = np.random.default_rng(20240411 + i)
-        CASES[i % 4](rng, i)
+        CASES[i % len(CASES)](rng, i)
