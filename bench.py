@@ -157,20 +157,19 @@ class Step:
     def run(self, verify_events=None, all_events=None):
         """verify_events: one event pair around the L back-to-back verification launches of
         this step (two records per step keep the timed region undisturbed); all_events: one
-        pair around every call (used outside the timed region for the breakdown)."""
+        pair around every kind of call -- the L layer calls of a pass share one pair, as they run
+        back to back -- (used outside the timed region for the breakdown)."""
         def call(name, fn, *args):
             if all_events is not None:
                 all_events.append((name, *_timed(lambda: fn(*args))))
             else:
                 fn(*args)
-        for l in range(self.L):
-            call("decode_attn_retrieval", self.draft_attn, l)
+        call("decode_attn_retrieval", lambda: [self.draft_attn(l) for l in range(self.L)])
         call("spec_accept", self.accept, self.acc_draft)
         if verify_events is not None:
             verify_events.append(_timed(lambda: [self.verify_attn(l) for l in range(self.L)]))
         else:
-            for l in range(self.L):
-                call("decode_attn_full", self.verify_attn, l)
+            call("decode_attn_full", lambda: [self.verify_attn(l) for l in range(self.L)])
         call("spec_accept", self.accept, self.acc_verify)
         call("chunk_summarize(new chunks)", self.summarize_new)
         call("chunk_topk_gather", self.rebuild)
