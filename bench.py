@@ -103,6 +103,11 @@ class Step:
                      tf.tf_chunk_topk_gather_workspace_bytes(LB, H, w.M, w.k),
                      tf.tf_spec_accept_workspace_bytes(B, w.G, w.V))
         self.ws = tf.workspace(nbytes, device)
+        # per-layer views, sliced once (a slice costs the host a few us, as much as the call itself)
+        self.draft_args = [tuple(self.layer(t, l) for t in (self.Q_d, self.Kr, self.Vr, self.O_d, self.LSE_d))
+                           for l in range(self.L)]
+        self.verify_args = [tuple(self.layer(t, l) for t in (self.Q, self.K, self.V, self.O, self.LSE))
+                            for l in range(self.L)]
 
     def layer(self, t, l):
         return t[l * self.w.B:(l + 1) * self.w.B]
@@ -121,14 +126,10 @@ class Step:
                                      self.Kr, self.Vr, ws=self.ws)
 
     def draft_attn(self, l):
-        self.tf.tf_decode_attn_retrieval(self.layer(self.Q_d, l), self.layer(self.Kr, l), self.layer(self.Vr, l),
-                                         self.layer(self.O_d, l), self.layer(self.LSE_d, l), scale=1.0,
-                                         causal=True, ws=self.ws)
+        self.tf.tf_decode_attn_retrieval(*self.draft_args[l], scale=1.0, causal=True, ws=self.ws)
 
     def verify_attn(self, l):
-        self.tf.tf_decode_attn_full(self.layer(self.Q, l), self.layer(self.K, l), self.layer(self.V, l),
-                                    self.layer(self.O, l), self.layer(self.LSE, l), scale=1.0, causal=True,
-                                    ws=self.ws)
+        self.tf.tf_decode_attn_full(*self.verify_args[l], scale=1.0, causal=True, ws=self.ws)
 
     def draft_attn_indexed(self, l):
         """Gather-free variant of the draft pass: through the chunk indices into the full cache;
