@@ -24,6 +24,7 @@
 // that, where batch x heads allows, exactly one workgroup runs per CU (see plan_splits).
 // The 16 columns of the QK^T MFMA hold up to 16 query rows, so the query heads of a
 // grouped-query KV head share its pass; head dim 128 or 64.
+#include <atomic>
 #include <type_traits>
 
 #include "tf_common.hpp"
@@ -436,18 +437,18 @@ int set_attn_option(bool retrieval, int64_t v) {
     return TF_OK;
 }
 
-// compute units of the current device (256 on a full MI355X), queried once
+// compute units of the current device (256 on a full MI355X), queried once per device
 static int num_cus() {
-    static int cached = 0;
-    if (cached == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cached = n;
-        else
-            cached = 256;
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];  // zero-initialised; 0 = not asked yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached;
+    return n;
 }
 
 // Split planning. Measured on MI355X with streaming (nt) loads: the fewer workgroups stream
@@ -467,15 +468,15 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
     int64_t tps = retrieval ? g_tps_retr : g_tps_full;
     if (tps == 0) {
         struct Memo {
-            int64_t BH, len;
+            int64_t BH, len, cus;
             int64_t tps;
         };
-        static thread_local Memo memo[3] = {{0, 0, 0}, {0, 0, 0}, {0, 0, 0}};
+        static thread_local Memo memo[3] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
         Memo &mm = memo[mode];
-        if (mm.BH == BH && mm.len == kv_len_all) {
+        const int64_t cus = num_cus();
+        if (mm.BH == BH && mm.len == kv_len_all && mm.cus == cus) {
             tps = mm.tps;
         } else {
-            const int64_t cus = num_cus();
             const int64_t min_tps = retrieval ? 128 : 512;  // shorter splits are all overhead
             int64_t ns_cap = kv_len_all / min_tps;
             if (ns_cap > kMaxSplits) ns_cap = kMaxSplits;   // the merge kernel stages one weight per split
@@ -497,6 +498,7 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
             }
             mm.BH = BH;
             mm.len = kv_len_all;
+            mm.cus = cus;
             mm.tps = tps;
         }
     }
