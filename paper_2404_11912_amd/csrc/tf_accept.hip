@@ -8,12 +8,14 @@
 // vocabulary of every logits row is cut into segments of 4096 entries, one workgroup each, so
 // a sequence's work spreads over many CUs. Three kernels on one stream:
 //   rowstats  per (row, segment): maximum (with its first index) and sum of exponentials;
-//   mass      per (sequence, segment): replays the accept walk (cheap), then computes the
+//   mass      per (sequence, segment): combines the segment records into the statistics of all
+//             2G-1 rows (32 lanes per row), replays the accept walk (cheap), then computes the
 //             per-thread partial sums of the distribution to draw from -- the residual
 //             max(p-q,0) of the rejected position, or p of the bonus position -- in index order;
-//   decide    per sequence: accept walk, prefix sums over segment and thread partials, and the
-//             owner thread walks its 4 entries for the inverse-CDF draw. A plain whole-row path
-//             in the same kernel covers the rare cases (all-zero residual, rounding at a cell edge).
+//   decide    per sequence: the same row statistics and accept walk, prefix sums over segment and
+//             thread partials, and the owner thread walks its 4 entries for the inverse-CDF draw.
+//             A plain whole-row path in the same kernel covers the rare cases (all-zero residual,
+//             rounding at a cell edge).
 #include "tf_common.hpp"
 
 namespace tf {
@@ -122,47 +124,76 @@ __global__ __launch_bounds__(kAccThreads) void accept_rowstats_kernel(const Acce
 }
 
 // statistics of a whole row from its segments: zmax = max(x)/T, sum = sum exp(x/T - zmax),
-// arg = first arg-max. Every thread computes the same values in the same order.
+// arg = first arg-max
 struct RowStats {
     double zmax, sum;
     int arg;
 };
+constexpr int kMaxRows = 2 * TF_MAX_SPEC - 1;  // target rows 0..G-1, then draft rows
 
-__device__ __forceinline__ RowStats combine_row(const AcceptParams &p, int b, int rr) {
-    const double *st = p.seg_stats + ((int64_t)b * (2 * p.G - 1) + rr) * p.S * 4;
-    double mx = st[0];
-    int arg = (int)st[2];
-    for (int s = 1; s < p.S; ++s)
-        if (st[s * 4] > mx) {  // strictly greater: ties keep the earlier segment's (lower) index
-            mx = st[s * 4];
-            arg = (int)st[s * 4 + 2];
+// All 2G-1 rows of sequence b at once, by the whole workgroup: 32 lanes per row, a lane takes
+// every 32nd segment (one fp64 exponential each at V <= 131072) and shuffles finish the row.
+// A thread that walked a row's segments alone would spend 2 x S dependent exponentials per row,
+// which was most of the latency of the two kernels below. Every workgroup that calls this gets
+// bit-identical values (same inputs, same order), so they all take the same decisions.
+// Ends with a barrier; rows[] is then valid for every thread.
+__device__ __forceinline__ void combine_rows(const AcceptParams &p, int b, RowStats *rows /* LDS [kMaxRows] */) {
+    const int n_rows = 2 * p.G - 1;
+    const int rr = threadIdx.x >> 5, l = threadIdx.x & 31;  // 1024 threads = 32 rows x 32 lanes
+    if (rr < n_rows) {
+        const double *st = p.seg_stats + ((int64_t)b * n_rows + rr) * p.S * 4;
+        double mx = -INFINITY;
+        int arg = kNone;
+        for (int s = l; s < p.S; s += 32) {
+            const double m = st[s * 4];
+            const int a = (int)st[s * 4 + 2];
+            if (m > mx || (m == mx && a < arg)) {  // ties: the lower vocabulary index
+                mx = m;
+                arg = a;
+            }
         }
-    RowStats r;
-    r.arg = arg;
-    r.zmax = 0.0;
-    r.sum = 0.0;
-    if (p.T != 0.0) {
-        r.zmax = mx / p.T;
-        for (int s = 0; s < p.S; ++s)
-            if (st[s * 4] != -INFINITY) r.sum += st[s * 4 + 1] * exp(st[s * 4] / p.T - r.zmax);
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) {
+            const double om = __shfl_xor(mx, off, kWave);
+            const int oa = __shfl_xor(arg, off, kWave);
+            if (om > mx || (om == mx && oa < arg)) {
+                mx = om;
+                arg = oa;
+            }
+        }
+        double sum = 0.0, zmax = 0.0;
+        if (p.T != 0.0) {
+            zmax = mx / p.T;
+            for (int s = l; s < p.S; s += 32) {
+                const double m = st[s * 4];
+                if (m != -INFINITY) sum += st[s * 4 + 1] * exp(m / p.T - zmax);
+            }
+#pragma unroll
+            for (int off = 16; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+        }
+        if (l == 0) {
+            rows[rr].zmax = zmax;
+            rows[rr].sum = sum;
+            rows[rr].arg = arg == kNone ? 0 : arg;
+        }
     }
-    return r;
+    __syncthreads();
 }
 
 // Accept walk of sequence b by the first wave: lane i tests drafted position i, a ballot finds
 // the first rejection. Returns n (valid in every lane of the calling wave).
-__device__ __forceinline__ int accept_walk(const AcceptParams &p, int b, int lane) {
+__device__ __forceinline__ int accept_walk(const AcceptParams &p, int b, int lane, const RowStats *rows) {
     const int gamma = p.G - 1, mine = drafted(p, b);
     bool ok = true;
     if (lane < mine) {
         const int tok = p.toks[(int64_t)b * gamma + lane];
         ok = tok >= 0 && tok < p.V;
         if (ok) {
-            const RowStats t = combine_row(p, b, lane);
+            const RowStats t = rows[lane];
             if (p.T == 0.0) {
                 ok = tok == t.arg;
             } else {
-                const RowStats d = combine_row(p, b, p.G + lane);
+                const RowStats d = rows[p.G + lane];
                 const double pt = exp((double)logits_row(p, b, lane)[tok] / p.T - t.zmax) / t.sum;
                 const double qt = exp((double)logits_row(p, b, p.G + lane)[tok] / p.T - d.zmax) / d.sum;
                 ok = (double)p.ua[(int64_t)b * gamma + lane] * qt < pt;
@@ -189,19 +220,21 @@ struct DrawDist {
 __global__ __launch_bounds__(kAccThreads) void accept_mass_kernel(const AcceptParams p) {
     __shared__ int s_n;
     __shared__ double wtot[kAccThreads / 64];
+    __shared__ RowStats rows[kMaxRows];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seg = blockIdx.x % p.S, b = blockIdx.x / p.S;
     const int gamma = p.G - 1;
+    combine_rows(p, b, rows);
     if (tid < 64) {
-        const int n = accept_walk(p, b, lane);
+        const int n = accept_walk(p, b, lane, rows);
         if (tid == 0) s_n = n;
     }
     __syncthreads();
     const int n = s_n;
     const bool rejected = n < drafted(p, b);
-    const RowStats ts = combine_row(p, b, n);
+    const RowStats ts = rows[n];
     RowStats ds = ts;
-    if (rejected) ds = combine_row(p, b, p.G + n);
+    if (rejected) ds = rows[p.G + n];
     const DrawDist dist{p.T, ts.zmax, ts.sum, ds.zmax, ds.sum, !rejected};
     const float *tl = logits_row(p, b, n);
     const float *dl = rejected ? logits_row(p, b, p.G + n) : tl;
@@ -235,14 +268,16 @@ __global__ __launch_bounds__(kAccThreads) void accept_mass_kernel(const AcceptPa
 __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const AcceptParams p) {
     __shared__ int s_n, s_tok, s_last;
     __shared__ double wtot[kAccThreads / 64];
+    __shared__ RowStats rows[kMaxRows];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
     const int gamma = p.G - 1;
     const int32_t *x = p.toks + (int64_t)b * gamma;
     int32_t *out = p.out + (int64_t)b * p.G;
 
+    combine_rows(p, b, rows);
     if (tid < 64) {
-        const int n = accept_walk(p, b, lane);
+        const int n = accept_walk(p, b, lane, rows);
         if (tid == 0) {
             s_n = n;
             s_tok = kNone;
@@ -252,7 +287,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const Accept
     __syncthreads();
     const int n = s_n;
     const bool rejected = n < drafted(p, b);
-    const RowStats ts = combine_row(p, b, n);
+    const RowStats ts = rows[n];
 
     if (p.T == 0.0) {
         if (tid == 0) {
@@ -263,7 +298,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_decide_kernel(const Accept
         return;
     }
     RowStats ds = ts;
-    if (rejected) ds = combine_row(p, b, p.G + n);
+    if (rejected) ds = rows[p.G + n];
     DrawDist dist{p.T, ts.zmax, ts.sum, ds.zmax, ds.sum, !rejected};
     const float *tl = logits_row(p, b, n);
     const float *dl = rejected ? logits_row(p, b, p.G + n) : tl;
