@@ -7,10 +7,12 @@
 //           per lane against the resident query, three shuffles per row finish the dot product.
 //   select  one 1024-thread workgroup per (b,h): exact radix select (4 x 8 bits, LDS
 //           histograms) of the k-th largest order-preserving key, ordered compaction of the
-//           winners (ties toward the lower chunk index), bitonic sort of the <= 2048 winners
-//           on (score desc, index asc) in LDS.
+//           winners (ties toward the lower chunk index), then every winner's place on
+//           (score desc, index asc) by counting the winners above it in LDS.
 //   gather  one wave per selected chunk copies its rows (256 B each) of K and V with 16-byte
 //           loads and stores.
+#include <type_traits>
+
 #include "tf_common.hpp"
 
 namespace tf {
@@ -230,6 +232,11 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wave_t
     return before + incl - v;
 }
 
+// kKeep > 0: a thread holds the keys of its contiguous index range [tid*per, tid*per+per),
+// per <= kKeep, in registers -- the scores are read from memory once, and the four radix passes
+// and the compaction run out of the register file (16 or 32 keys; 64 would spill at 1024 threads).
+// kKeep == 0 (over 32768 chunks per head): every pass streams the scores again.
+template <int kKeep>
 __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *__restrict__ scores,
                                                                   int64_t score_stride,
                                                                   const int32_t *__restrict__ n_chunks, int n_all,
@@ -248,6 +255,41 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *_
     const int k_eff = min(k, n);
     const float *sc = scores + bh * score_stride;
 
+    // thread t owns the contiguous index range [i_lo, i_hi); per is a multiple of 4 and the score
+    // rows are padded to one, so the range is read as whole float4
+    int per = (n + kSelThreads - 1) / kSelThreads;
+    per = (per + 3) & ~3;
+    const int i_lo = min(tid * per, n), i_hi = min(n, i_lo + per);
+
+    uint32_t keys[kKeep > 0 ? kKeep : 1];
+    if constexpr (kKeep > 0) {
+#pragma unroll
+        for (int u = 0; u < kKeep; u += 4) {
+            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k_eff > 0 && i_lo + u < i_hi) f = *reinterpret_cast<const float4 *>(sc + i_lo + u);
+            keys[u] = score_key(f.x);
+            keys[u + 1] = score_key(f.y);
+            keys[u + 2] = score_key(f.z);
+            keys[u + 3] = score_key(f.w);
+        }
+    }
+    // f(key, index) for every key of this thread's range, in increasing index order
+    auto for_owned = [&](auto &&f) {
+        if constexpr (kKeep > 0) {
+#pragma unroll
+            for (int u = 0; u < kKeep; ++u)
+                if (i_lo + u < i_hi) f(keys[u], i_lo + u);
+        } else {
+            for (int i = i_lo; i < i_hi; i += 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(sc + i);
+                const float fv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i + u < i_hi) f(score_key(fv[u]), i + u);
+            }
+        }
+    };
+
     // ---- radix select: key of the k_eff-th largest score -------------------------------
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)k_eff;
     if (k_eff > 0) {
@@ -255,9 +297,15 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *_
             const int shift = 24 - 8 * pass;
             if (tid < 256) hist[tid] = 0;
             __syncthreads();
-            for (int i = tid; i < n; i += kSelThreads) {
-                const uint32_t key = score_key(sc[i]);
-                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            if constexpr (kKeep > 0) {
+                for_owned([&](uint32_t key, int) {
+                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                });
+            } else {
+                for (int i = tid; i < n; i += kSelThreads) {  // order does not matter here: coalesced
+                    const uint32_t key = score_key(sc[i]);
+                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                }
             }
             __syncthreads();
             // waves 0..3: suffix sums over the 256 bins (bin = tid)
@@ -293,76 +341,46 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *_
     const uint32_t T = prefix;                        // key of the k_eff-th largest
     const uint32_t n_gt = (uint32_t)k_eff - remaining;  // keys strictly above T (all kept)
 
-    // ---- ordered compaction: thread t owns the contiguous index range [t*per, (t+1)*per) --
-    int per = (n + kSelThreads - 1) / kSelThreads;
-    per = (per + 3) & ~3;
-    const int i_lo = tid * per, i_hi = min(n, i_lo + per);
+    // ---- ordered compaction of the winners (ties toward the lower index) ------------------
     uint32_t c_gt = 0, c_eq = 0;
-    if (k_eff > 0) {
-        for (int i = i_lo; i < i_hi; i += 4) {
-            const float4 f = *reinterpret_cast<const float4 *>(sc + i);
-            const float fv[4] = {f.x, f.y, f.z, f.w};
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (i + u < i_hi) {
-                    const uint32_t key = score_key(fv[u]);
-                    c_gt += key > T;
-                    c_eq += key == T;
-                }
-        }
-    }
+    if (k_eff > 0)
+        for_owned([&](uint32_t key, int) {
+            c_gt += key > T;
+            c_eq += key == T;
+        });
     uint32_t tot_gt, tot_eq;
     uint32_t p_gt = block_excl_scan(c_gt, wtot, &tot_gt);
     uint32_t p_eq = block_excl_scan(c_eq, wtot, &tot_eq);
-    if (k_eff > 0) {
-        for (int i = i_lo; i < i_hi; i += 4) {
-            const float4 f = *reinterpret_cast<const float4 *>(sc + i);
-            const float fv[4] = {f.x, f.y, f.z, f.w};
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (i + u < i_hi) {
-                    const uint32_t key = score_key(fv[u]);
-                    const unsigned long long comp =
-                        ((unsigned long long)key << 32) | (unsigned long long)(0xffffffffu - (uint32_t)(i + u));
-                    if (key > T) {
-                        cand[p_gt++] = comp;
-                    } else if (key == T) {
-                        if (p_eq < remaining) cand[n_gt + p_eq] = comp;
-                        ++p_eq;
-                    }
-                }
-        }
-    }
-    int kp = 1;
-    while (kp < k_eff) kp <<= 1;
-    for (int j = k_eff + tid; j < kp; j += kSelThreads) cand[j] = 0ull;  // below every real entry
-
-    // ---- bitonic sort, descending on (key, ~index) ---------------------------------------
-    for (int size = 2; size <= kp; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int t = tid; t < (kp >> 1); t += kSelThreads) {
-                const int lo = 2 * t - (t & (stride - 1));
-                const int hi = lo + stride;
-                const bool desc = (lo & size) == 0;
-                const unsigned long long a = cand[lo], c = cand[hi];
-                if ((a < c) == desc) {
-                    cand[lo] = c;
-                    cand[hi] = a;
-                }
+    if (k_eff > 0)
+        for_owned([&](uint32_t key, int i) {
+            const unsigned long long comp =
+                ((unsigned long long)key << 32) | (unsigned long long)(0xffffffffu - (uint32_t)i);
+            if (key > T) {
+                cand[p_gt++] = comp;
+            } else if (key == T) {
+                if (p_eq < remaining) cand[n_gt + p_eq] = comp;
+                ++p_eq;
             }
-        }
-    }
+        });
     __syncthreads();
-    for (int j = tid; j < k; j += kSelThreads) {
-        int32_t idx = -1;
-        float val = -INFINITY;
-        if (j < k_eff) {
-            idx = (int32_t)(0xffffffffu - (uint32_t)(cand[j] & 0xffffffffull));
-            val = sc[idx];
-        }
-        out_idx[bh * k + j] = idx;
-        if (out_score) out_score[bh * k + j] = val;
+
+    // ---- order the winners: descending on (key, ~index) -----------------------------------
+    // The composite values are distinct, so the place of a winner is the number of winners above
+    // it. Counting that directly -- every thread walks the whole list, all lanes reading the same
+    // LDS word per turn (a broadcast) -- takes k_eff turns without a barrier, against the
+    // log^2(k) barrier-separated stages of a sorting network (45 stages for 512 winners).
+    for (int j = tid; j < k_eff; j += kSelThreads) {
+        const unsigned long long mine = cand[j];
+        int above = 0;
+#pragma unroll 8
+        for (int i = 0; i < k_eff; ++i) above += cand[i] > mine;
+        const int32_t idx = (int32_t)(0xffffffffu - (uint32_t)(mine & 0xffffffffull));
+        out_idx[bh * k + above] = idx;
+        if (out_score) out_score[bh * k + above] = sc[idx];
+    }
+    for (int j = k_eff + tid; j < k; j += kSelThreads) {  // fewer chunks than k: the rest is empty
+        out_idx[bh * k + j] = -1;
+        if (out_score) out_score[bh * k + j] = -INFINITY;
     }
 }
 
@@ -453,9 +471,14 @@ int topk_gather_launch(const void *q_r, const void *Kmean, int64_t M_cap, const 
     else
         hipLaunchKernelGGL(chunk_score_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
 
-    hipLaunchKernelGGL(topk_select_kernel, dim3((unsigned)BH), dim3(kSelThreads), 0, st, sp.scores,
-                       sp.score_stride, n_chunks, (int)n_chunks_all, (int)kd->heads, (int)k_chunks, out_idx,
-                       out_score);
+    auto select = [&](auto keep_tag) {
+        hipLaunchKernelGGL((topk_select_kernel<decltype(keep_tag)::value>), dim3((unsigned)BH), dim3(kSelThreads), 0,
+                           st, sp.scores, sp.score_stride, n_chunks, (int)n_chunks_all, (int)kd->heads,
+                           (int)k_chunks, out_idx, out_score);
+    };
+    if (n_chunks_all <= 16 * kSelThreads) select(std::integral_constant<int, 16>{});
+    else if (n_chunks_all <= 32 * kSelThreads) select(std::integral_constant<int, 32>{});
+    else select(std::integral_constant<int, 0>{});
 
     if (do_gather) {
         GatherParams gp;

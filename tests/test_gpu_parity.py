@@ -433,6 +433,28 @@ def test_topk_maximum_k_and_many_chunks():
                                 torch.empty((B, H, k + 1), dtype=torch.int32, device=DEV))
 
 
+@pytest.mark.parametrize("M", [16384, 16385, 32768, 32769])
+def test_topk_select_register_tiers(M):
+    """Chunk counts on both sides of the limits where the select kernel keeps 16 keys per thread in
+    registers, 32, or streams the scores on every pass; the second sequence is shorter."""
+    say(f"case topk_tiers M={M} seed=125")
+    rng = np.random.default_rng(125 + M)
+    B, H, k = 2, 2, 300
+    km = rng.standard_normal((B, H, M, 128)).astype(np.float32)
+    q = bf16_u16(rng.standard_normal((B, H, 128)) * 0.3)
+    nc = [M, M - 4097]
+    idx = torch.empty((B, H, k), dtype=torch.int32, device=DEV)
+    score = torch.empty((B, H, k), dtype=torch.float32, device=DEV)
+    K = torch.zeros((B, H, M, 128), dtype=torch.bfloat16, device=DEV)
+    tf.tf_chunk_topk_gather(u16_torch(q, DEV), torch.from_numpy(km).to(DEV), K, K, 1, k, idx, out_score=score,
+                            n_chunks=torch.tensor(nc, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    got, gs = idx.cpu().numpy(), score.cpu().numpy().astype(np.float64)
+    for b in range(B):
+        o_scores, o_idx = oracle.retrieve(q[b:b + 1], km[b:b + 1, :, :nc[b]].astype(np.float64), k)
+        check_topk(got[b:b + 1], gs[b:b + 1], o_scores, o_idx, [nc[b]], k, tag=f"tiers M={M} b={b}")
+
+
 def test_attn_eight_queries_many_splits():
     say("case attn_G8_many_splits seed=108")
     x = synth.make_layer(1, 2, 20000 + 9, 8, 8, 4, seed=108)
