@@ -122,6 +122,16 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     // LDS, and 16 VGPRs fewer per lane buy a third wave per SIMD): entry [kk][lane] holds
     // Q[query r][32kk + 8s .. +8] for lane (r,s), zero for r >= G
     __shared__ uint4 sm_q[kNK][kWave];
+    // indexed mode: the chunk indices this split walks, staged once (a global index load in front
+    // of every row load would put two memory latencies in series per tile)
+    constexpr int kIdxStage = kIndexed ? 1024 : 1;
+    __shared__ int32_t sm_idx[kIdxStage];
+    const int j_first = kIndexed ? t_begin / p.chunk : 0;  // first chunk slot of this split
+    if constexpr (kIndexed) {
+        const int j_end = min(p.k_chunks, (t_end + p.chunk - 1) / p.chunk);
+        for (int j = j_first + tid; j < min(j_end, j_first + kIdxStage); j += 256)
+            sm_idx[j - j_first] = p.idx[(int64_t)bh * p.k_chunks + j];
+    }
     if (wave == 0) {
 #pragma unroll
         for (int kk = 0; kk < kNK; ++kk) {
@@ -150,7 +160,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         int row = -1;
         if (v < kc_tokens) {
             const int j = v / p.chunk;
-            const int m = p.idx[(int64_t)bh * p.k_chunks + j];
+            const int m = j - j_first < kIdxStage ? sm_idx[j - j_first] : p.idx[(int64_t)bh * p.k_chunks + j];
             if (m >= 0 && (int64_t)(m + 1) * p.chunk <= (int64_t)p.full_len_all) row = m * p.chunk + (v - j * p.chunk);
         } else if (v < len) {
             row = rb + (v - kc_tokens);

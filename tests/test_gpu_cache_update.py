@@ -51,6 +51,26 @@ def test_indexed_attention_vs_oracle(c, k, G):
     assert e <= ATTN_TOL and el <= LSE_TOL
 
 
+def test_indexed_attention_split_with_more_chunks_than_the_kernel_stages():
+    """One split that walks 1500 single-token chunks: the kernel keeps the first 1024 chunk indices
+    of a split on chip and reads the rest from memory."""
+    say("case indexed_long_split seed=158")
+    B, H, N, c, k, G = 1, 2, 4000, 1, 1500, 2
+    x = synth.make_layer(B, H, N, G, c, 0, seed=158)
+    rng = np.random.default_rng(158)
+    idx = np.stack([np.stack([rng.permutation(N - 100)[:k] for _ in range(H)]) for _ in range(B)]).astype(np.int32)
+    idx[0, 0, 1400] = -1
+    tf.tf_set_option("attn_retr_tokens_per_split", 2048)
+    try:
+        O, L = _run_indexed(x["Q"].to(DEV), x["K"].to(DEV), x["V"].to(DEV), torch.from_numpy(idx).to(DEV), c,
+                            kv_len_all=N, recent_begin_all=N - 10)
+    finally:
+        tf.tf_set_option("attn_retr_tokens_per_split", 0)
+    Oo, Lo = oracle.attention_indexed(synth.as_u16(x["Q"]), synth.as_u16(x["K"]), synth.as_u16(x["V"]), idx, c,
+                                      kv_len=[N], recent_begin=[N - 10], kv_len_all=N)
+    assert float(np.max(np.abs(O - Oo))) <= ATTN_TOL and float(np.max(np.abs(L - Lo))) <= LSE_TOL
+
+
 def test_indexed_matches_retrieval_attention_over_the_gathered_cache():
     """The same draft attention two ways on the GPU: through the indices, and over the gathered
     retrieval cache with the recent rows appended behind it."""
