@@ -469,8 +469,9 @@ static int num_cus() {
 // splits are equal, the one with the smallest modelled time
 //     (workgroups on the busiest CU) x (tokens per split) / rate(workgroups per CU),
 // which is "one workgroup per CU" whenever batch x heads divides the CU count.
-// The indexed form chases an index before every row (a dependent load), so it is latency-bound and
-// wants the opposite: three workgroups per CU (19 us against 23.5 us per layer at a 4K budget).
+// The indexed form reads scattered chunks (a few KiB each) instead of one long stream, so it is
+// latency-bound and wants the opposite: three workgroups per CU (19 us against 23.5 us per layer at
+// a 4K budget).
 enum PlanMode { kPlanFull = 0, kPlanRetrieval = 1, kPlanIndexed = 2 };
 
 static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
