@@ -36,7 +36,8 @@ def build_oracle(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build_oracle())
+        # TF_ORACLE_LIB: a test that plants a mistake in a copy of tf_oracle.c points the pins at it
+        _lib = ctypes.CDLL(os.environ.get("TF_ORACLE_LIB") or build_oracle())
         _lib.orc_num_threads.restype = ctypes.c_int
         for name in ("orc_attention", "orc_chunk_mean", "orc_retrieve", "orc_gather", "orc_accept"):
             getattr(_lib, name).restype = ctypes.c_int
