@@ -362,7 +362,9 @@ def main():
                   "decode_attn_full_cold_us_per_layer": None if cold_us is None else round(cold_us, 1)},
         "roofline": {"bound": "hbm", "kernel": "attn_split_kernel (tf_decode_attn_full)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     # the counter summary was taken on step128k's launches (2 GiB per launch)
+                     "traffic": read_traffic_note() if w.name == "step128k" else None,
                      "algorithmic_bytes_per_launch": w.kv_bytes_per_layer(),
                      "avg_launch_us": round(verify_avg_s * 1e6, 2), "launches_timed": len(verify_ms) * L},
     }
