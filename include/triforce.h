@@ -32,7 +32,9 @@
  *     stream, passed as `void* stream` (a hipStream_t; NULL = the default stream). Scratch
  *     memory comes from a caller-provided workspace `ws` of at least the size the matching
  *     *_workspace_bytes() query returns (256-byte aligned); calls sharing one workspace must
- *     be ordered on one stream.
+ *     be ordered on one stream. The attention queries are monotone in the length: a workspace
+ *     queried for kv_len_all = X (same batch, heads, G and knobs) serves every call with
+ *     kv_len_all <= X.
  *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE fp32), fp32 is IEEE float.
  *   - Strides are in ELEMENTS. head_dim must be contiguous (stride 1) and 128; the attention
  *     calls (full, retrieval, indexed, tree) and tf_kv_append also accept 64, the head size of
@@ -85,17 +87,26 @@ typedef struct tf_kv_desc {
 int tf_version(void);                   /* major*10000 + minor*100 + patch */
 const char *tf_status_string(int code); /* static string, never NULL */
 
-/* Tuning knobs (host state, not thread-safe against concurrent calls). Known names:
+/* Tuning knobs. Known names:
  *   "attn_full_tokens_per_split", "attn_retr_tokens_per_split"  (multiples of 64; 0 = auto),
  *   "score_steps_per_wave" (16-chunk steps a wave of the scoring kernel takes; 0 = auto).
- * Returns TF_ERR_INVALID_ARG for an unknown name or bad value. Workspace queries reflect the
- * knobs in force when they are called. */
+ * tf_set_option sets the process-wide default (an atomic: safe to call while other threads run
+ * calls, which pick up either the old or the new value). tf_set_thread_option sets an override that
+ * only the CALLING host thread's later workspace queries and calls see (value -1 removes it), so
+ * threads that drive different streams can tune independently. Every call reads its knobs once and
+ * plans, checks the workspace and launches from that one reading. Workspace queries reflect the
+ * knobs the calling thread sees when they are made; change a knob between query and call and the
+ * call may answer TF_ERR_WORKSPACE (never overrun the workspace).
+ * Returns TF_ERR_INVALID_ARG for an unknown name or bad value. */
 int tf_set_option(const char *name, int64_t value);
+int tf_set_thread_option(const char *name, int64_t value);
 
 /* ---------------------------------------------------------------------------------------
  * tf_chunk_summarize -- Sec. 4.1: every chunk of the KV cache is summarised by the mean of its keys.
  *   Kmean[b,h,m,:] = (1/chunk) * sum_{i<chunk} K[b,h,m*chunk+i,:]   for
- *   m in [first_chunk, first_chunk+n_chunks), every (b,h). fp32 sums of bf16 keys.
+ *   m in [first_chunk, first_chunk+n_chunks), every (b,h). Arithmetic, fixed so that the result
+ *   is reproducible bit for bit: the chunk's keys are widened to fp32 and added in token order
+ *   to a sum starting at +0 (each addition rounded to fp32), then one IEEE fp32 division by chunk.
  *   K      in   bf16, described by kd; (first_chunk+n_chunks)*chunk <= kd->capacity
  *   Kmean  out  fp32 [batch, heads, M_cap, 128] contiguous; other rows untouched
  *   The range arguments allow summarising only newly completed chunks. n_chunks == 0 is a
@@ -134,7 +145,9 @@ int tf_chunk_topk_gather(const void *q_r, const float *Kmean, int64_t M_cap, con
 /* ---------------------------------------------------------------------------------------
  * tf_chunk_summarize_bf16 / tf_chunk_topk_gather_bf16 -- the same two operations (Sec. 4.1) with
  * the average-key table held in bf16: half the table's memory and half the scoring traffic.
- *   Kmean_bf16[b,h,m,:] = the fp32 mean of tf_chunk_summarize rounded to bf16 (nearest even);
+ *   Kmean_bf16[b,h,m,:] = the fp32 mean exactly as tf_chunk_summarize computes it (sequential fp32
+ *   sum in token order, one fp32 division), then rounded to bf16, nearest even: two roundings, so
+ *   about one entry in 10^5..10^6 is one bf16 ulp away from the exact mean rounded once;
  *   scores are fp32 dot products of q_r with the widened bf16 entries; everything else
  *   (selection order, ties, gather, arguments, workspace size, errors) as in the fp32 calls.
  * A table written by tf_chunk_summarize_bf16 must be read by tf_chunk_topk_gather_bf16.
@@ -170,6 +183,18 @@ int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv
                         const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
                         int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes,
                         void *stream);
+
+/* The launch shape an attention call would take now (split-K over the KV sequence, Algorithm 1's
+ * two attention passes): kind 0 = tf_decode_attn_full / tf_decode_attn_tree, 1 =
+ * tf_decode_attn_retrieval, 2 = tf_decode_attn_indexed (len_all = k_chunks*chunk + recent rows).
+ * Writes the number of splits per (batch, head) unit and the tokens per split to the two HOST
+ * integers. Informational (profiling, tests); depends on the knobs the calling thread sees and on
+ * the current device's compute-unit count. */
+#define TF_PLAN_FULL 0
+#define TF_PLAN_RETRIEVAL 1
+#define TF_PLAN_INDEXED 2
+int tf_decode_attn_plan(int32_t kind, int32_t batch, int32_t heads, int64_t len_all, int32_t *nsplit,
+                        int32_t *tokens_per_split);
 
 /* ---------------------------------------------------------------------------------------
  * tf_decode_attn_tree -- verification of a speculated token TREE (Sec. 5.3.3, the combination with
@@ -218,7 +243,7 @@ int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const 
  * gathered cache followed by the same recent rows, without the copy. idx is int32
  * [batch, heads, k_chunks]; the caller keeps selected chunks and the recent range disjoint.
  * Other arguments as in tf_decode_attn_full. k_chunks >= 0; chunk in [1, 64];
- * workspace: pass an upper bound of len[b]-rb[b] as recent_len_all.
+ * workspace: pass an upper bound of kv_len_all - recent_begin_all as recent_len_all.
  * ------------------------------------------------------------------------------------- */
 size_t tf_decode_attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chunks,
                                               int32_t chunk, int64_t recent_len_all, int32_t G);

@@ -13,6 +13,8 @@ from .tf_oracle import (  # noqa: F401
     build_oracle,
     chunk_mean,
     chunk_mean_bf16,
+    chunk_mean_bf16_once,
+    chunk_mean_fp32,
     gather,
     kv_append,
     num_threads,

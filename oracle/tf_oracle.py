@@ -100,9 +100,35 @@ def round_to_bf16(x) -> np.ndarray:
     return np.ldexp(np.rint(m * 256.0), e - 8)
 
 
+def chunk_mean_fp32(K, c: int) -> np.ndarray:
+    """The average key of every chunk (Sec. 4.1) as an IEEE fp32 computation with a fixed order:
+    the chunk's c keys are widened to fp32 and added one after the other in token order to a sum
+    that starts at +0, every addition rounded to fp32; then one fp32 division by c. This is the
+    value the bf16 table is defined from (see chunk_mean_bf16): a table entry is a quantised code,
+    so the precision in which it is decided has to be fixed, and it is fixed to this.
+    K [B,H,N,d] uint16(bf16) -> float32 [B,H,N//c,d]."""
+    K = _u16(K)
+    B, H, N, d = K.shape
+    M = N // c
+    rows = (K[:, :, :M * c].astype(np.uint32) << 16).view(np.float32).reshape(B, H, M, c, d)
+    acc = np.zeros((B, H, M, d), dtype=np.float32)
+    for i in range(c):                          # one rounded fp32 addition per key
+        acc = (acc + rows[:, :, :, i]).astype(np.float32)
+    return (acc / np.float32(c)).astype(np.float32)
+
+
 def chunk_mean_bf16(K, c: int) -> np.ndarray:
-    """Average keys held in bf16 (variant of Sec. 4.1's average-key table): the exact chunk mean,
-    rounded once to bf16. Returned as float64 [B,H,M,d] holding bf16-representable values."""
+    """Average keys held in bf16 (variant of Sec. 4.1's average-key table). Definition, the same
+    on both sides of the parity tests: the fp32 chunk mean of chunk_mean_fp32 (sequential fp32 sum
+    in token order, one fp32 division), rounded to bf16 by round-to-nearest-even. Two roundings:
+    in rare cases (about one entry in 10^5..10^6) the result differs by one bf16 ulp from the
+    exact mean rounded once. Returned as float64 [B,H,M,d] holding bf16-representable values."""
+    return round_to_bf16(chunk_mean_fp32(K, c).astype(np.float64))
+
+
+def chunk_mean_bf16_once(K, c: int) -> np.ndarray:
+    """The exact (fp64) chunk mean rounded once to bf16: not the table's definition, kept to state
+    how far the two-rounding definition is from it (tests bound the difference)."""
     return round_to_bf16(chunk_mean(K, c))
 
 

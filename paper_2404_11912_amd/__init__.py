@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     tf_decode_attn_full,
     tf_decode_attn_indexed,
     tf_decode_attn_indexed_workspace_bytes,
+    tf_decode_attn_plan,
     tf_kv_append,
     tf_decode_attn_tree,
     tf_chunk_summarize_bf16,
@@ -28,6 +29,7 @@ from .binding import (  # noqa: F401
     tf_decode_attn_retrieval,
     tf_decode_attn_retrieval_workspace_bytes,
     tf_set_option,
+    tf_set_thread_option,
     tf_spec_accept,
     tf_spec_accept_workspace_bytes,
     tf_version,

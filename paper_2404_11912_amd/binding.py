@@ -20,7 +20,7 @@ TF_MAX_K_CHUNKS = 2048
 TF_MAX_SPEC = 16
 
 EXPORTS = (
-    "tf_version", "tf_status_string", "tf_set_option",
+    "tf_version", "tf_status_string", "tf_set_option", "tf_set_thread_option", "tf_decode_attn_plan",
     "tf_chunk_summarize",
     "tf_chunk_topk_gather_workspace_bytes", "tf_chunk_topk_gather",
     "tf_decode_attn_full_workspace_bytes", "tf_decode_attn_full",
@@ -65,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     lib.tf_status_string.argtypes = [ctypes.c_int]
     lib.tf_set_option.restype = ctypes.c_int
     lib.tf_set_option.argtypes = [ctypes.c_char_p, i64]
+    lib.tf_set_thread_option.restype = ctypes.c_int
+    lib.tf_set_thread_option.argtypes = [ctypes.c_char_p, i64]
     lib.tf_chunk_summarize.restype = ctypes.c_int
     lib.tf_chunk_summarize.argtypes = [vp, dp, i32, i64, i64, vp, i64, vp]
     lib.tf_chunk_summarize_bf16.restype = ctypes.c_int
@@ -81,6 +83,8 @@ def load_library() -> ctypes.CDLL:
         getattr(lib, name + "_workspace_bytes").argtypes = [i32, i32, i64, i32]
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, i32, vp, vp, vp, sz, vp]
+    lib.tf_decode_attn_plan.restype = ctypes.c_int
+    lib.tf_decode_attn_plan.argtypes = [i32, i32, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.tf_decode_attn_indexed_workspace_bytes.restype = sz
     lib.tf_decode_attn_indexed_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i32]
     lib.tf_decode_attn_indexed.restype = ctypes.c_int
@@ -138,12 +142,29 @@ def workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def _temp_workspace(nbytes: int, device, stream) -> torch.Tensor:
+    """Scratch for one call when the caller passed none. The tensor is dropped as soon as the call
+    has enqueued its kernels, so the block must belong to the stream the kernels run on: the caching
+    allocator hands a freed block back only to later work of the stream it was allocated on, which
+    is then ordered behind those kernels. (Allocated on another stream, the block could be given to
+    that stream's next allocation while the kernels still use it.)"""
+    if stream is None:
+        return workspace(nbytes, device)
+    with torch.cuda.stream(stream):
+        return workspace(nbytes, device)
+
+
 def tf_version() -> int:
     return int(load_library().tf_version())
 
 
 def tf_set_option(name: str, value: int) -> None:
     _check("tf_set_option", load_library().tf_set_option(name.encode(), int(value)))
+
+
+def tf_set_thread_option(name: str, value: int) -> None:
+    """Override a knob for the calling host thread only (-1 removes the override)."""
+    _check("tf_set_thread_option", load_library().tf_set_thread_option(name.encode(), int(value)))
 
 
 def tf_chunk_summarize_bf16(K, chunk: int, Kmean, first_chunk: int = 0, n_chunks: int | None = None, stream=None):
@@ -191,21 +212,34 @@ def tf_chunk_topk_gather(q_r, Kmean, K, V, chunk: int, k_chunks: int, out_idx, K
     kv_desc(V)
     if V.stride() != K.stride() or V.shape != K.shape:
         raise ValueError("K and V must share shape and strides")
+    if Kmean.dim() != 4 or tuple(Kmean.shape[:2]) != (d.batch, d.heads) or Kmean.shape[3] != d.head_dim:
+        raise ValueError("Kmean must be [B,H,M_cap,d]")
+    if tuple(q_r.shape) != (d.batch, d.heads, d.head_dim):
+        raise ValueError("q_r must be [B,H,d]")
+    if tuple(out_idx.shape) != (d.batch, d.heads, int(k_chunks)):
+        raise ValueError("out_idx must be [B,H,k_chunks]")
     M_cap = Kmean.shape[2]
     if n_chunks_all is None:
         n_chunks_all = min(M_cap, K.shape[2] // chunk)
     if n_chunks is not None:
         _need(n_chunks, torch.int32, "n_chunks")
+        if tuple(n_chunks.shape) != (d.batch,):
+            raise ValueError("n_chunks must be [B]")
     if out_score is not None:
         _need(out_score, torch.float32, "out_score")
+        if tuple(out_score.shape) != (d.batch, d.heads, int(k_chunks)):
+            raise ValueError("out_score must be [B,H,k_chunks]")
     rd = None
     if Kr is not None or Vr is not None:
         rd = kv_desc(Kr)
         kv_desc(Vr)
         if Vr.stride() != Kr.stride() or Vr.shape != Kr.shape:
             raise ValueError("Kr and Vr must share shape and strides")
+        if (rd.batch, rd.heads, rd.head_dim) != (d.batch, d.heads, d.head_dim):
+            raise ValueError("Kr, Vr must be [B,H,R_cap,d] with the cache's B, H, d")
     if ws is None:
-        ws = workspace(tf_chunk_topk_gather_workspace_bytes(d.batch, d.heads, n_chunks_all, k_chunks), K.device)
+        ws = _temp_workspace(tf_chunk_topk_gather_workspace_bytes(d.batch, d.heads, n_chunks_all, k_chunks),
+                             K.device, stream)
     _check(_name,
            getattr(lib, _name)(_ptr(q_r), _ptr(Kmean), int(M_cap), _ptr(K), _ptr(V), ctypes.byref(d),
                                int(chunk), _ptr(n_chunks), int(n_chunks_all), int(k_chunks),
@@ -235,12 +269,14 @@ def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream, 
             raise ValueError("LSE must be [B,H,G]")
     if kv_len is not None:
         _need(kv_len, torch.int32, "kv_len")
+        if tuple(kv_len.shape) != (d.batch,):
+            raise ValueError("kv_len must be [B]")
     if kv_len_all is None:
         kv_len_all = K.shape[2]
     if ws is None:
         ws_name = "tf_decode_attn_full" if tail_mask is not None else name
         nbytes = getattr(lib, ws_name + "_workspace_bytes")(d.batch, d.heads, int(kv_len_all), int(G) * d.q_group)
-        ws = workspace(nbytes, K.device)
+        ws = _temp_workspace(nbytes, K.device, stream)
     if tail_mask is not None:
         rows = [int(m) for m in tail_mask]
         if len(rows) != G or any(m < 0 or m > 0xffff for m in rows):
@@ -252,6 +288,15 @@ def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream, 
                                     int(G), float(scale), mask_arg, _ptr(O), _ptr(LSE), _ptr(ws),
                                     ws.numel() * ws.element_size(), _stream(stream)))
     return O
+
+
+def tf_decode_attn_plan(kind: int, batch: int, heads: int, len_all: int):
+    """(splits per (b,h) unit, tokens per split) an attention call would take now; kind 0 = full /
+    tree, 1 = retrieval, 2 = indexed."""
+    ns, tps = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check("tf_decode_attn_plan", load_library().tf_decode_attn_plan(int(kind), int(batch), int(heads), int(len_all),
+                                                                    ctypes.byref(ns), ctypes.byref(tps)))
+    return ns.value, tps.value
 
 
 def tf_decode_attn_full_workspace_bytes(batch: int, heads: int, kv_len_all: int, G: int) -> int:
@@ -311,10 +356,16 @@ def tf_decode_attn_indexed(Q, K, V, idx, chunk: int, O, LSE=None, kv_len=None, k
         raise ValueError("O must be [B,H,G,d]")
     if LSE is not None:
         _need(LSE, torch.float32, "LSE")
+        if tuple(LSE.shape) != tuple(Q.shape[:3]):
+            raise ValueError("LSE must be [B,H*q_group,G]")
     if kv_len is not None:
         _need(kv_len, torch.int32, "kv_len")
+        if tuple(kv_len.shape) != (d.batch,):
+            raise ValueError("kv_len must be [B]")
     if recent_begin is not None:
         _need(recent_begin, torch.int32, "recent_begin")
+        if tuple(recent_begin.shape) != (d.batch,):
+            raise ValueError("recent_begin must be [B]")
     if kv_len_all is None:
         kv_len_all = K.shape[2]
     if recent_begin_all is None:
@@ -322,7 +373,7 @@ def tf_decode_attn_indexed(Q, K, V, idx, chunk: int, O, LSE=None, kv_len=None, k
     if ws is None:
         nbytes = lib.tf_decode_attn_indexed_workspace_bytes(d.batch, d.heads, int(k), int(chunk),
                                                             int(kv_len_all - recent_begin_all), int(G) * d.q_group)
-        ws = workspace(nbytes, K.device)
+        ws = _temp_workspace(nbytes, K.device, stream)
     _check("tf_decode_attn_indexed",
            lib.tf_decode_attn_indexed(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(idx), int(k), int(chunk),
                                       _ptr(kv_len), int(kv_len_all), _ptr(recent_begin), int(recent_begin_all),
@@ -379,7 +430,7 @@ def tf_spec_accept(target_logits, draft_logits, draft_tokens, temperature: float
     if tuple(u_sample.shape) != (B,) or tuple(n_accepted.shape) != (B,) or tuple(out_tokens.shape) != (B, G):
         raise ValueError("u_sample / n_accepted must be [B], out_tokens [B,G]")
     if ws is None:
-        ws = workspace(tf_spec_accept_workspace_bytes(B, G, V), target_logits.device)
+        ws = _temp_workspace(tf_spec_accept_workspace_bytes(B, G, V), target_logits.device, stream)
     if n_draft is not None:
         _need(n_draft, torch.int32, "n_draft")
         if tuple(n_draft.shape) != (B,):

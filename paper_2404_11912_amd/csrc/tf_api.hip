@@ -16,8 +16,9 @@ int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, co
                 float, int32_t, float *, float *, void *, size_t, void *, bool, const IndexedArgs *, const uint16_t *);
 int kv_append_launch(const void *, const void *, int32_t, void *, void *, const tf_kv_desc *, const int32_t *,
                      int64_t, void *);
-int set_attn_option(bool retrieval, int64_t v);
-int set_score_option(int64_t v);
+int attn_plan(int32_t, int32_t, int32_t, int64_t, int32_t *, int32_t *);
+int set_attn_option(bool retrieval, int64_t v, bool this_thread);
+int set_score_option(int64_t v, bool this_thread);
 size_t accept_workspace_bytes(int32_t, int32_t, int32_t);
 int accept_launch(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, float, const float *,
                   const float *, int32_t *, int32_t *, void *, size_t, void *, const int32_t *);
@@ -38,13 +39,17 @@ const char *tf_status_string(int code) {
     }
 }
 
-int tf_set_option(const char *name, int64_t value) {
+static int set_option(const char *name, int64_t value, bool this_thread) {
     if (!name) return TF_ERR_INVALID_ARG;
-    if (!strcmp(name, "attn_full_tokens_per_split")) return tf::set_attn_option(false, value);
-    if (!strcmp(name, "attn_retr_tokens_per_split")) return tf::set_attn_option(true, value);
-    if (!strcmp(name, "score_steps_per_wave")) return tf::set_score_option(value);
+    if (!strcmp(name, "attn_full_tokens_per_split")) return tf::set_attn_option(false, value, this_thread);
+    if (!strcmp(name, "attn_retr_tokens_per_split")) return tf::set_attn_option(true, value, this_thread);
+    if (!strcmp(name, "score_steps_per_wave")) return tf::set_score_option(value, this_thread);
     return TF_ERR_INVALID_ARG;
 }
+
+int tf_set_option(const char *name, int64_t value) { return set_option(name, value, false); }
+
+int tf_set_thread_option(const char *name, int64_t value) { return set_option(name, value, true); }
 
 int tf_chunk_summarize(const void *K, const tf_kv_desc *kd, int32_t chunk, int64_t first_chunk, int64_t n_chunks,
                        float *Kmean, int64_t M_cap, void *stream) {
@@ -74,6 +79,11 @@ int tf_chunk_topk_gather_bf16(const void *q_r, const void *Kmean, int64_t M_cap,
                               const tf_kv_desc *rd, void *ws, size_t ws_bytes, void *stream) {
     return tf::topk_gather_launch(q_r, Kmean, M_cap, K, V, kd, chunk, n_chunks, n_chunks_all, k_chunks, out_idx,
                                   out_score, Kr, Vr, rd, ws, ws_bytes, stream, true);
+}
+
+int tf_decode_attn_plan(int32_t kind, int32_t batch, int32_t heads, int64_t len_all, int32_t *nsplit,
+                        int32_t *tokens_per_split) {
+    return tf::attn_plan(kind, batch, heads, len_all, nsplit, tokens_per_split);
 }
 
 size_t tf_decode_attn_full_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G) {

@@ -439,12 +439,26 @@ struct SplitPlan {
     int tokens_per_split;
 };
 
-static int64_t g_tps_full = 0, g_tps_retr = 0;  // 0 = automatic
+// Tokens per split, 0 = automatic. A process-wide default (atomic: may be set while other threads
+// call) and a per-thread override (-1 = none) that only the calling thread's later queries and
+// calls see, so two host threads driving two streams can tune independently.
+static std::atomic<int64_t> g_tps_full{0}, g_tps_retr{0};
+static thread_local int64_t t_tps_full = -1, t_tps_retr = -1;
 
-int set_attn_option(bool retrieval, int64_t v) {
+int set_attn_option(bool retrieval, int64_t v, bool this_thread) {
+    if (this_thread && v == -1) {
+        (retrieval ? t_tps_retr : t_tps_full) = -1;
+        return TF_OK;
+    }
     if (v < 0 || (v % 64) != 0 || v > (1 << 30)) return TF_ERR_INVALID_ARG;
-    (retrieval ? g_tps_retr : g_tps_full) = v;
+    if (this_thread) (retrieval ? t_tps_retr : t_tps_full) = v;
+    else (retrieval ? g_tps_retr : g_tps_full).store(v, std::memory_order_relaxed);
     return TF_OK;
+}
+
+static int64_t tps_option(bool retrieval) {
+    const int64_t t = retrieval ? t_tps_retr : t_tps_full;
+    return t >= 0 ? t : (retrieval ? g_tps_retr : g_tps_full).load(std::memory_order_relaxed);
 }
 
 // compute units of the current device (256 on a full MI355X), queried once per device
@@ -473,10 +487,12 @@ static int num_cus() {
 // latency-bound and wants the opposite: three workgroups per CU (19 us against 23.5 us per layer at
 // a 4K budget).
 enum PlanMode { kPlanFull = 0, kPlanRetrieval = 1, kPlanIndexed = 2 };
+// shorter splits are all overhead
+static int64_t min_tokens_per_split(PlanMode mode) { return mode != kPlanFull ? 128 : 512; }
 
 static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
     const bool retrieval = mode != kPlanFull;
-    int64_t tps = retrieval ? g_tps_retr : g_tps_full;
+    int64_t tps = tps_option(retrieval);
     if (tps == 0) {
         struct Memo {
             int64_t BH, len, cus;
@@ -488,8 +504,7 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
         if (mm.BH == BH && mm.len == kv_len_all && mm.cus == cus) {
             tps = mm.tps;
         } else {
-            const int64_t min_tps = retrieval ? 128 : 512;  // shorter splits are all overhead
-            int64_t ns_cap = kv_len_all / min_tps;
+            int64_t ns_cap = kv_len_all / min_tokens_per_split(mode);
             if (ns_cap > kMaxSplits) ns_cap = kMaxSplits;   // the merge kernel stages one weight per split
             const int64_t ns_useful = (8 * cus + BH - 1) / BH;  // beyond 8 workgroups per CU nothing changes
             if (ns_cap > ns_useful) ns_cap = ns_useful;
@@ -525,14 +540,44 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
 // sized for head dim 128 whatever the call's head dim (the queries do not take it); 8 query rows per
 // KV head, 16 when there are more than 8
 static int rows_of(int G) { return G > 8 ? 16 : 8; }
-static size_t attn_ws_bytes(int64_t BH, const SplitPlan &sp, int G) {
-    return (size_t)BH * sp.nsplit * (rows_of(G) * kHeadDim + 2 * rows_of(G)) * sizeof(float);
+static size_t attn_ws_bytes(int64_t BH, int64_t nsplit, int G) {
+    return (size_t)BH * nsplit * (rows_of(G) * kHeadDim + 2 * rows_of(G)) * sizeof(float);
+}
+
+// The most splits any call with a length in [1, len_bound] can plan under the options in force.
+// The planned count itself is not monotone in the length (it snaps to counts that fill the CUs
+// evenly), so the workspace queries size for this bound: a workspace queried for some length then
+// serves every call with that length or less.
+static int64_t max_splits_upto(int64_t BH, int64_t len_bound, PlanMode mode) {
+    const bool retrieval = mode != kPlanFull;
+    const int64_t tps = tps_option(retrieval);
+    int64_t ns;
+    if (tps > 0) {
+        ns = (len_bound + tps - 1) / tps;
+    } else {
+        ns = len_bound / min_tokens_per_split(mode);
+        const int64_t ns_useful = (8 * (int64_t)num_cus() + BH - 1) / BH;
+        if (ns > ns_useful) ns = ns_useful;
+    }
+    if (ns > kMaxSplits) ns = kMaxSplits;
+    return ns < 1 ? 1 : ns;
+}
+
+// the launch shape a call with these sizes would take now (for callers that want to know, and tests)
+int attn_plan(int32_t kind, int32_t batch, int32_t heads, int64_t len_all, int32_t *nsplit, int32_t *tokens_per_split) {
+    if (kind < 0 || kind > 2 || batch <= 0 || heads <= 0 || len_all <= 0 || !nsplit || !tokens_per_split)
+        return TF_ERR_INVALID_ARG;
+    if (len_all > (int64_t)1 << 30) return TF_ERR_UNSUPPORTED;
+    const SplitPlan sp = plan_splits((int64_t)batch * heads, len_all, (PlanMode)kind);
+    *nsplit = sp.nsplit;
+    *tokens_per_split = sp.tokens_per_split;
+    return TF_OK;
 }
 
 size_t attn_workspace_bytes(int32_t batch, int32_t heads, int64_t kv_len_all, int32_t G, bool retrieval) {
     if (batch <= 0 || heads <= 0 || kv_len_all <= 0 || G <= 0) return 0;
     const int64_t BH = (int64_t)batch * heads;
-    return attn_ws_bytes(BH, plan_splits(BH, kv_len_all, retrieval ? kPlanRetrieval : kPlanFull), G);
+    return attn_ws_bytes(BH, max_splits_upto(BH, kv_len_all, retrieval ? kPlanRetrieval : kPlanFull), G);
 }
 
 
@@ -546,7 +591,7 @@ size_t attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chun
     const int64_t lv = (int64_t)k_chunks * chunk + recent_len_all;
     if (lv <= 0) return 0;
     const int64_t BH = (int64_t)batch * heads;
-    return attn_ws_bytes(BH, plan_splits(BH, lv, kPlanIndexed), G);
+    return attn_ws_bytes(BH, max_splits_upto(BH, lv, kPlanIndexed), G);
 }
 
 int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd, const int32_t *kv_len,
@@ -578,7 +623,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     const int64_t BH = (int64_t)kd->batch * kd->heads;
     const SplitPlan sp = plan_splits(BH, plan_len, ix ? kPlanIndexed : (retrieval ? kPlanRetrieval : kPlanFull));
     if (BH * sp.nsplit >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
-    if (!ws || !aligned(ws, 256) || ws_bytes < attn_ws_bytes(BH, sp, GQ)) return TF_ERR_WORKSPACE;
+    if (!ws || !aligned(ws, 256) || ws_bytes < attn_ws_bytes(BH, sp.nsplit, GQ)) return TF_ERR_WORKSPACE;
 
     AttnParams p;
     p.Q = static_cast<const uint16_t *>(Q);

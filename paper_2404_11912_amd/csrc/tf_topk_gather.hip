@@ -11,6 +11,7 @@
 //           (score desc, index asc) by counting the winners above it in LDS.
 //   gather  one wave per selected chunk copies its rows (256 B each) of K and V with 16-byte
 //           loads and stores.
+#include <atomic>
 #include <type_traits>
 
 #include "tf_common.hpp"
@@ -19,12 +20,23 @@ namespace tf {
 
 constexpr int kScoreMaxIters = 16;  // 16-row steps per wave (a workgroup covers 4 x 16 x iters rows)
 constexpr int kSelThreads = 1024;
-static int64_t g_score_iters = 0;  // 0 = automatic
+// 16-row steps per wave of the scoring kernel, 0 = automatic: a process-wide default (atomic) and a
+// per-thread override (-1 = none), as for the attention split options
+static std::atomic<int64_t> g_score_iters{0};
+static thread_local int64_t t_score_iters = -1;
 
-int set_score_option(int64_t v) {
+int set_score_option(int64_t v, bool this_thread) {
+    if (this_thread && v == -1) {
+        t_score_iters = -1;
+        return TF_OK;
+    }
     if (v < 0 || v > 4096) return TF_ERR_INVALID_ARG;
-    g_score_iters = v;
+    if (this_thread) t_score_iters = v;
+    else g_score_iters.store(v, std::memory_order_relaxed);
     return TF_OK;
+}
+static int64_t score_iters_option() {
+    return t_score_iters >= 0 ? t_score_iters : g_score_iters.load(std::memory_order_relaxed);
 }
 
 struct ScoreParams {
@@ -163,7 +175,7 @@ __global__ __launch_bounds__(256) void chunk_score_bf16_kernel(const ScoreParams
         float mine = 0.f;
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            float a = q[0] * bf16lo(v[rr].x);
+            float a = fmaf(q[0], bf16lo(v[rr].x), 0.f);  // from +0, so that a zero score is +0 (never -0) as in the fp32 kernel
             a = fmaf(q[1], bf16hi(v[rr].x), a);
             a = fmaf(q[2], bf16lo(v[rr].y), a);
             a = fmaf(q[3], bf16hi(v[rr].y), a);
@@ -461,7 +473,7 @@ int topk_gather_launch(const void *q_r, const void *Kmean, int64_t M_cap, const 
     // keep at least ~2048 workgroups in the launch
     int64_t iters = n_chunks_all * BH / (64 * 2048);
     iters = iters < 1 ? 1 : (iters > kScoreMaxIters ? kScoreMaxIters : iters);
-    if (g_score_iters > 0) iters = g_score_iters;
+    if (const int64_t forced = score_iters_option(); forced > 0) iters = forced;
     sp.iters = (int32_t)iters;
     sp.blocks_per_bh = (int32_t)((n_chunks_all + 64 * iters - 1) / (64 * iters));
     sp.scores = static_cast<float *>(ws);

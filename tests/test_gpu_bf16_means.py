@@ -1,7 +1,9 @@
-"""GPU parity of the bf16 average-key variant (tf_chunk_summarize_bf16, tf_chunk_topk_gather_bf16):
-the table holds the chunk means rounded once to bf16; scoring, selection and gather are otherwise
-those of the fp32 calls. Selection parity is judged on scores the oracle computes from the same
-bf16 table, so the 1e-4 tie band of the fp32 path applies unchanged."""
+"""GPU parity of the bf16 average-key variant (tf_chunk_summarize_bf16, tf_chunk_topk_gather_bf16).
+One definition on both sides: a table entry is the fp32 chunk mean (sequential fp32 sum in token
+order, one fp32 division) rounded to bf16, nearest even. The device's table must equal the oracle's
+BIT FOR BIT; the device's selection is judged against the oracle's selection on the ORACLE's table
+(no device value ever enters the oracle), with the 1e-4 tie band of the fp32 path: the tables being
+equal, the scores differ only by the fp32 rounding of a 128-term dot product."""
 import numpy as np
 import pytest
 import torch
@@ -21,7 +23,8 @@ def say(msg):
     print(msg, flush=True)
 
 
-def table_f64(Kmean_bf16):
+def device_table(Kmean_bf16):
+    """The device's table widened exactly to float64 (compared with the oracle's, never fed to it)."""
     return u16_f64(synth.as_u16(Kmean_bf16.cpu()))
 
 
@@ -35,17 +38,27 @@ def test_summarize_bf16(c):
     tf.tf_chunk_summarize_bf16(K, c, Kmean)
     torch.cuda.synchronize()
     want = oracle.chunk_mean_bf16(synth.as_u16(x["K"]), c)
-    got = table_f64(Kmean)
-    diff = got != want
-    frac = float(diff.mean())
-    say(f"[bf16 means c={c}] entries differing from the once-rounded exact mean: {frac:.2e}")
-    # The device rounds twice (fp32 sum and division, then bf16); the oracle rounds the exact mean once.
-    # The two differ only when the fp32 result falls on the other side of a bf16 rounding boundary:
-    # rare (about one entry in 10^5 .. 10^6, less for power-of-two chunks whose division is exact),
-    # and then by one bf16 ulp.
-    assert frac < (1e-4 if c & (c - 1) == 0 else 1e-3)
-    if diff.any():
-        assert np.max(np.abs(got - want)[diff] / np.abs(want[diff])) <= 2.0 ** -7
+    assert np.array_equal(device_table(Kmean), want)          # bit-equal: same two roundings on both sides
+
+
+def test_summarize_bf16_on_the_double_rounding_example():
+    """A chunk on which rounding the fp32 mean differs from rounding the exact mean once (keys 4,
+    12/256, -2^-30, 0: fp32 mean exactly halfway -> even -> 1 + 2^-6; exact mean rounds to
+    1 + 2^-7), and one whose fp32 sum depends on the order of the additions."""
+    say("case bf16 means double rounding by hand")
+    K = torch.zeros((1, 1, 16, 128), dtype=torch.float64)
+    K[0, 0, 0:4] = torch.tensor([4.0, 12.0 / 256.0, -2.0 ** -30, 0.0], dtype=torch.float64)[:, None]
+    K[0, 0, 4:8] = torch.tensor([2.0 ** 24, 1.0, 1.0, 1.0], dtype=torch.float64)[:, None]
+    K[0, 0, 8:12] = torch.tensor([1.0, 1.0, 1.0, 2.0 ** 24], dtype=torch.float64)[:, None]
+    Kb = K.to(torch.bfloat16)
+    assert torch.equal(Kb.double(), K)
+    Kmean = torch.zeros((1, 1, 4, 128), dtype=torch.bfloat16, device=DEV)
+    tf.tf_chunk_summarize_bf16(Kb.to(DEV), 4, Kmean)
+    torch.cuda.synchronize()
+    got = device_table(Kmean)
+    assert np.all(got[0, 0, 0] == 1 + 2.0 ** -6)
+    assert np.all(got[0, 0, 1] == 2.0 ** 22) and np.all(got[0, 0, 2] == 2.0 ** 22)   # 2^22 + 1 is no bf16 value
+    assert np.array_equal(got, oracle.chunk_mean_bf16(synth.as_u16(Kb), 4))
 
 
 @pytest.mark.parametrize("N,c,k,P", [(4096, 8, 64, 8), (32768, 8, 512, 64), (8192, 16, 100, 16), (3000, 4, 37, 4)])
@@ -63,8 +76,9 @@ def test_topk_gather_bf16_vs_oracle(N, c, k, P):
     Vr = torch.zeros_like(Kr)
     tf.tf_chunk_topk_gather_bf16(q_r, Kmean, K, V, c, k, idx, Kr, Vr, out_score=score)
     torch.cuda.synchronize()
-    # the oracle scores the device's own table (an exact widening; the table itself is checked above)
-    o_scores, o_idx = oracle.retrieve(synth.as_u16(x["q_r"]), table_f64(Kmean), k)
+    o_table = oracle.chunk_mean_bf16(synth.as_u16(x["K"]), c)
+    assert np.array_equal(device_table(Kmean), o_table)
+    o_scores, o_idx = oracle.retrieve(synth.as_u16(x["q_r"]), o_table, k)
     idx_h, sc_h = idx.cpu().numpy(), score.cpu().numpy().astype(np.float64)
     same = 0
     for b in range(B):
@@ -103,7 +117,9 @@ def test_bf16_table_per_sequence_counts_and_ties():
     tf.tf_chunk_topk_gather_bf16(q_r, Kmean, Kd, Vd, c, k, idx, n_chunks=torch.tensor(nc, device=DEV),
                                  n_chunks_all=M)
     torch.cuda.synchronize()
-    o_scores, o_idx = oracle.retrieve(synth.as_u16(x["q_r"]), table_f64(Kmean), k, n_chunks=nc)
+    o_table = oracle.chunk_mean_bf16(synth.as_u16(K), c)
+    assert np.array_equal(device_table(Kmean), o_table)
+    o_scores, o_idx = oracle.retrieve(synth.as_u16(x["q_r"]), o_table, k, n_chunks=nc)
     got = idx.cpu().numpy()
     assert got[1].max() < 100
     g00 = got[0, 0].tolist()
@@ -133,8 +149,10 @@ def test_bf16_table_at_the_128k_layer_shape():
     tf.tf_chunk_topk_gather_bf16(q_r, Kb, K, V, w.c, w.k, idx_b)
     tf.tf_chunk_topk_gather(q_r, Kf, K, V, w.c, w.k, idx_f)
     torch.cuda.synchronize()
-    assert torch.equal(Kb, Kf.to(torch.bfloat16))             # torch's conversion is the same single rounding
-    o_scores, o_idx = oracle.retrieve(synth.as_u16(q_r), table_f64(Kb), w.k)
+    assert torch.equal(Kb, Kf.to(torch.bfloat16))             # the bf16 table is the fp32 table rounded (nearest even)
+    o_table = oracle.chunk_mean_bf16(synth.as_u16(K.cpu()), w.c)   # 1 GiB of keys through the oracle: seconds
+    assert np.array_equal(device_table(Kb), o_table)
+    o_scores, o_idx = oracle.retrieve(synth.as_u16(q_r.cpu()), o_table, w.k)
     got = idx_b.cpu().numpy()
     planted = x["planted"].cpu().numpy()
     overlap = []

@@ -22,9 +22,9 @@ def say(msg):
 
 
 @pytest.mark.parametrize("name,layer", [
-    ("step128k", 0), ("step128k", 31),
-    ("batch4x64k", 1),
-    ("extreme1m", 1),
+    ("step128k", 0), ("step128k", 31),                             # first and last layer of each of the
+    ("batch4x64k", 0), ("batch4x64k", 1), ("batch4x64k", 31),      # three big workloads, every unit
+    ("extreme1m", 0), ("extreme1m", 1), ("extreme1m", 7),
     ("batch2x56k", 0), ("batch6x19k", 3), ("batch10x12k", 31),     # batch shapes of Table 4
 ])
 def test_one_layer_at_full_size(name, layer):
@@ -135,6 +135,54 @@ def test_accept_batch4_vocab_32000(gamma):
     assert np.array_equal(n.cpu().numpy(), n_o) and np.array_equal(out.cpu().numpy(), out_o)
 
 
+@pytest.mark.parametrize("gamma", [2, 6])
+def test_batch4x64k_attention_with_other_draft_lengths(gamma):
+    """The batch-4 workload speculates gamma in {2, 4, 6} tokens (4 is the workload's default and is
+    covered above): verification attention with G = 3 and 7 queries on the full 4 x 64K layer shape,
+    every unit, and the draft attention of the same G over the gathered retrieval cache with the
+    queries' own tokens staged behind the budget (kv_len = R + G, bottom-right causal mask)."""
+    import dataclasses
+    G = gamma + 1
+    w = dataclasses.replace(synth.WORKLOADS["batch4x64k"], G=G)
+    say(f"case fullsize batch4x64k layer=5 G={G} seed={synth.seed_for(w, 5)}")
+    x = synth.make_workload_layer(w, 5, DEV)
+    K, V, Q, q_r = x["K"], x["V"], x["Q"], x["q_r"]
+    B, H, N, d = K.shape
+    assert Q.shape[2] == G
+    O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+    L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_full(Q, K, V, O, L, causal=True)
+    Kmean = torch.empty((B, H, w.M, d), dtype=torch.float32, device=DEV)
+    tf.tf_chunk_summarize(K, w.c, Kmean, 0, w.M)
+    idx = torch.empty((B, H, w.k), dtype=torch.int32, device=DEV)
+    Kr = torch.zeros((B, H, w.R + G, d), dtype=torch.bfloat16, device=DEV)
+    Vr = torch.zeros_like(Kr)
+    tf.tf_chunk_topk_gather(q_r, Kmean, K, V, w.c, w.k, idx, Kr, Vr)
+    tf.tf_kv_append(K[:, :, N - G:].contiguous(), V[:, :, N - G:].contiguous(), Kr, Vr, pos_all=w.R)
+    O_d = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+    L_d = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_retrieval(Q, Kr, Vr, O_d, L_d, kv_len_all=w.R + G, causal=True)
+    torch.cuda.synchronize()
+    Ku, Vu, Qu = synth.as_u16(K), synth.as_u16(V), synth.as_u16(Q)
+    idx_h = idx.cpu().numpy()
+    del K, V, x, Kmean
+    torch.cuda.empty_cache()
+    Oo, Lo, _ = oracle.attention(Qu, Ku, Vu, scale=1.0, causal=True)
+    e = float(np.max(np.abs(O.cpu().numpy() - Oo)))
+    el = float(np.max(np.abs(L.cpu().numpy() - Lo)))
+    say(f"[batch4x64k G={G}] verify attention, all {B * H} units: max|dO|={e:.2e} max|dLSE|={el:.2e}")
+    assert e <= ATTN_TOL and el <= LSE_TOL
+    # draft cache by its definition, from the device's (valid) selection: chunks in that order, then
+    # the G newest rows; the selection itself is judged in the tests above
+    assert idx_h.min() >= 0 and idx_h.max() < w.M
+    Od, Ld = oracle.attention_indexed(Qu, Ku, Vu, idx_h, w.c, recent_begin=N - G, scale=1.0, causal=True)[:2]
+    ed = float(np.max(np.abs(O_d.cpu().numpy() - Od)))
+    eld = float(np.max(np.abs(L_d.cpu().numpy() - Ld)))
+    say(f"[batch4x64k G={G}] draft attention over the gathered cache + staged tokens: max|dO|={ed:.2e} "
+        f"max|dLSE|={eld:.2e}")
+    assert ed <= ATTN_TOL and eld <= LSE_TOL
+
+
 def test_batch_with_per_sequence_lengths_at_a_batching_shape():
     """The 6 x 19K batch shape of Table 4 with six different context lengths (a ragged batch, one
     of them not a multiple of the chunk or tile size): summaries, retrieval with per-sequence
@@ -192,7 +240,7 @@ def test_batch_with_per_sequence_lengths_at_a_batching_shape():
     assert ed <= ATTN_TOL and eld <= LSE_TOL
 
 
-@pytest.mark.parametrize("name,n_pairs", [("step128k", 64), ("batch4x64k", 16), ("extreme1m", 8)])
+@pytest.mark.parametrize("name,n_pairs", [("step128k", 64), ("batch4x64k", 64), ("extreme1m", 64)])
 def test_random_layer_head_pairs(name, n_pairs):
     """Seeded random (layer, batch, head) units spread over all layers of a workload: the whole
     layer runs on the device in the benchmark's launch configuration, the oracle checks the

@@ -156,6 +156,9 @@ def test_chunk_summarize(c):
     assert np.isnan(got[:, :, M:]).all()                  # rows outside the range untouched
     if c in (1, 4, 8, 16):
         assert float(np.max(np.abs(got[:, :, :M] - want))) < 2e-7
+    # the call fixes its arithmetic (sequential fp32 sum in token order, one fp32 division): bit-equal
+    # to the oracle's fp32 transcription of that definition
+    assert np.array_equal(Kmean.cpu().numpy()[:, :, :M], oracle.chunk_mean_fp32(synth.as_u16(x["K"]), c))
 
 
 def test_chunk_summarize_incremental_range():
@@ -266,6 +269,60 @@ def test_topk_exact_ties_go_to_lower_index():
     o_scores, o_idx = oracle.retrieve(q, km.astype(np.float64), k)
     # the 20 distinct rows are random, so distinct scores differ by far more than the band
     assert np.array_equal(idx, o_idx)
+
+
+def _retrieve_on_table(q_u16, km32, k, bf16_table):
+    """Run the selection on a given average-key table (values exact in bf16 when bf16_table)."""
+    B, H, M, _ = km32.shape
+    table = torch.from_numpy(km32).to(DEV)
+    if bf16_table:
+        assert torch.equal(table.to(torch.bfloat16).float(), table)
+        table = table.to(torch.bfloat16)
+    Kz = torch.zeros(B, H, M, 128, dtype=torch.bfloat16, device=DEV)
+    idx = torch.full((B, H, k), -7, dtype=torch.int32, device=DEV)
+    score = torch.empty((B, H, k), dtype=torch.float32, device=DEV)
+    fn = tf.tf_chunk_topk_gather_bf16 if bf16_table else tf.tf_chunk_topk_gather
+    fn(u16_torch(q_u16, DEV), table, Kz, Kz, 1, k, idx, out_score=score)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), score.cpu().numpy()
+
+
+@pytest.mark.parametrize("bf16_table", [False, True])
+def test_topk_zero_query_every_score_ties(bf16_table):
+    """q_r = 0: every score is zero whatever the signs of the averages (a product 0 * negative is
+    -0; the sum must still be +0 so that all scores compare equal): indices 0..k-1 in order."""
+    say(f"case topk_zero_query bf16_table={bf16_table}")
+    rng = np.random.default_rng(123)
+    B, H, M, k = 1, 3, 500, 37
+    km = (rng.integers(-8, 9, (B, H, M, 128)) / 4.0).astype(np.float32)
+    km[:, 1] = -np.abs(km[:, 1]) - 0.25                           # a head whose averages are all negative
+    km[:, 2, ::3] = -np.abs(km[:, 2, ::3]) - 0.25                 # and one where every third row is
+    q = np.zeros((B, H, 128), dtype=np.uint16)
+    q[:, 2, ::2] = 0x8000                                         # -0 entries in the query as well
+    idx, score = _retrieve_on_table(q, km, k, bf16_table)
+    _, o_idx = oracle.retrieve(q, km.astype(np.float64), k)
+    assert np.array_equal(o_idx, np.broadcast_to(np.arange(k), (B, H, k)))
+    assert np.array_equal(idx, o_idx)
+    assert np.all(score == 0.0) and not np.signbit(score).any()
+
+
+@pytest.mark.parametrize("bf16_table", [False, True])
+def test_topk_one_exactly_zero_score_among_others(bf16_table):
+    """Scores that are small exact integers (one query component is 1, the rest 0), among them
+    exactly one zero and rows whose other entries are negative: the order is fully determined and
+    must equal the oracle's."""
+    say(f"case topk_single_zero_score bf16_table={bf16_table}")
+    rng = np.random.default_rng(124)
+    B, H, M, k = 1, 2, 64, 40
+    km = -np.abs(rng.integers(1, 9, (B, H, M, 128)) / 2.0).astype(np.float32)
+    for h in range(H):
+        km[0, h, :, 5] = rng.permutation(M) - 30                  # scores -30 .. 33, each once, one of them 0
+    q = np.zeros((B, H, 128), dtype=np.uint16)
+    q[:, :, 5] = 0x3f80                                           # 1.0
+    idx, score = _retrieve_on_table(q, km, k, bf16_table)
+    o_scores, o_idx = oracle.retrieve(q, km.astype(np.float64), k)
+    assert np.array_equal(idx, o_idx)
+    assert np.array_equal(score.astype(np.float64), np.take_along_axis(o_scores, o_idx.astype(np.int64), axis=2))
 
 
 def test_topk_per_sequence_chunk_counts_and_full_budget():
@@ -529,3 +586,48 @@ def test_spec_accept_ragged(T):
     assert safe.all()
     assert np.array_equal(n.cpu().numpy(), n_o) and np.array_equal(out.cpu().numpy(), out_o)
     assert np.all(n_o <= nd)
+
+
+def test_spec_accept_zero_residual_falls_back_to_the_target_distribution():
+    """p = q (identical logits) and the drafted token on a masked (-inf) entry at some position:
+    there p(x) = q(x) = 0, so the test u q(x) < p(x) fails and the token is rejected, while the
+    residual max(p - q, 0) is zero everywhere: the correction is then drawn from p itself (the
+    kernel's whole-row path). u_sample runs from 0 to the largest fp32 below 1."""
+    say("case spec_accept zero residual seed=9950")
+    B, gamma, V, T = 12, 3, 9000, 0.8
+    a = synth.make_accept_inputs(B, gamma, V, T, 9950, correlated=True)
+    mask = np.zeros(V, dtype=bool)
+    mask[100:300] = True
+    mask[4096:8192] = True                       # one whole segment of the kernel
+    mask[8900:] = True                           # the tail: the last positive entry is not the last entry
+    a["target_logits"][..., mask] = -float("inf")
+    a["draft_logits"] = a["target_logits"][:, :gamma, :].clone()
+    keep = torch.nonzero(~torch.as_tensor(mask)).flatten()
+    toks = keep[a["draft_tokens"].long() % keep.numel()].to(torch.int32)
+    want_n = []
+    for b in range(B):
+        pos = b % (gamma + 1)                    # gamma: nothing rejected (bonus token from p_gamma)
+        if pos < gamma:
+            toks[b, pos] = 150 + b               # a masked entry
+        want_n.append(pos)
+    a["draft_tokens"] = toks
+    a["u_sample"] = torch.tensor([0.0, 0.5, 1.0 - 2.0 ** -24, 0.999, 1e-7, 0.25, 1.0 - 2.0 ** -24, 0.75, 0.1,
+                                  1.0 - 2.0 ** -23, 0.9, 0.3], dtype=torch.float32)
+    Tf = float(np.float32(T))
+    n_o, out_o, ma, ms = oracle.accept(a["target_logits"].numpy(), a["draft_logits"].numpy(), toks.numpy(), Tf,
+                                       a["u_accept"].numpy(), a["u_sample"].numpy())
+    assert n_o.tolist() == want_n                # p = q accepts every unmasked token, whatever u_accept
+    n = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    out = torch.full((B, gamma + 1), -9, dtype=torch.int32, device=DEV)
+    tf.tf_spec_accept(a["target_logits"].to(DEV), a["draft_logits"].to(DEV), toks.to(DEV), T, a["u_accept"].to(DEV),
+                      a["u_sample"].to(DEV), n, out)
+    torch.cuda.synchronize()
+    n, out = n.cpu().numpy(), out.cpu().numpy()
+    assert np.array_equal(n, n_o)
+    # the accept decisions here are exact on both sides (0 < 0 is false; u q < q is true for u < 1);
+    # only the draw's distance to a cell edge can make the two summation orders disagree
+    safe = ms > 1e-9
+    assert safe.sum() >= B - 2
+    assert np.array_equal(out[safe], out_o[safe])
+    drawn = out[np.arange(B), n]
+    assert not mask[drawn].any()                 # never a zero-probability token, also at u -> 1

@@ -50,36 +50,84 @@ def test_workspace_queries(lib):
     assert tf.tf_decode_attn_full_workspace_bytes(0, 32, 10, 1) == 0
 
 
-def _nsplit(fn, B, H, N, G):
-    return fn(B, H, N, G) // (B * H * (8 * 128 + 16) * 4)          # partials: 8 rows x (128 + 2) floats per split
+def _nsplit(kind, B, H, N):
+    return tf.tf_decode_attn_plan(kind, B, H, N)[0]
 
 
 def test_split_planning(lib):
     """Without a GPU the planner assumes 256 CUs. Long caches whose units divide the CU count get
     one workgroup per CU; others get equal splits on a whole number of workgroups per CU."""
-    full, retr = tf.tf_decode_attn_full_workspace_bytes, tf.tf_decode_attn_retrieval_workspace_bytes
-    assert _nsplit(full, 1, 32, 131072, 5) == 8
-    assert _nsplit(full, 1, 32, 1048576, 5) == 8
-    assert _nsplit(full, 4, 32, 65536, 5) == 2
-    assert _nsplit(full, 2, 32, 57344, 5) == 4
-    assert _nsplit(full, 6, 32, 19456, 5) == 4                      # 768 workgroups: three per CU
-    assert _nsplit(full, 10, 32, 12288, 5) == 4
-    assert _nsplit(retr, 1, 32, 4096, 3) == 8
-    assert _nsplit(full, 1, 1, 3, 3) == 1                           # never more splits than 512-token pieces
-    assert _nsplit(full, 1, 4, 4096, 5) == 8
-    assert _nsplit(full, 1, 1, 1 << 30, 8) <= 2048                  # the merge kernel's limit
-    assert tf.tf_decode_attn_indexed_workspace_bytes(1, 32, 512, 8, 3, 3) // (32 * (8 * 128 + 16) * 4) == 22
+    full, retr, indexed = 0, 1, 2
+    assert tf.tf_decode_attn_plan(full, 1, 32, 131072) == (8, 16384)
+    assert _nsplit(full, 1, 32, 1048576) == 8
+    assert _nsplit(full, 4, 32, 65536) == 2
+    assert _nsplit(full, 2, 32, 57344) == 4
+    assert _nsplit(full, 6, 32, 19456) == 4                         # 768 workgroups: three per CU
+    assert _nsplit(full, 10, 32, 12288) == 4
+    assert _nsplit(retr, 1, 32, 4096) == 8
+    assert _nsplit(full, 1, 1, 3) == 1                              # never more splits than 512-token pieces
+    assert _nsplit(full, 1, 4, 4096) == 8
+    assert _nsplit(full, 1, 1, 1 << 30) <= 2048                     # the merge kernel's limit
+    assert _nsplit(indexed, 1, 32, 512 * 8 + 3) == 22
+
+
+def test_workspace_queries_are_monotone_in_the_length(lib):
+    """The planned split count snaps to counts that fill the CUs evenly, so it is not monotone in
+    the length (4096 tokens of 32 units plan more splits than 4100); the workspace query sizes for
+    the most splits any shorter length could plan, so a workspace queried for a bound serves
+    every call below it."""
+    per_split = (8 * 128 + 16) * 4
+    for kind, query in ((0, tf.tf_decode_attn_full_workspace_bytes), (1, tf.tf_decode_attn_retrieval_workspace_bytes)):
+        for BH in (1, 4, 32, 192):
+            prev = 0
+            for n in list(range(1, 300, 7)) + list(range(3900, 4400, 9)) + [8192, 65536, 131072]:
+                ws = query(1, BH, n, 5)
+                assert ws >= prev
+                prev = ws
+                assert ws >= BH * _nsplit(kind, 1, BH, n) * per_split
+    q = tf.tf_decode_attn_indexed_workspace_bytes
+    assert q(1, 32, 512, 8, 64, 3) >= 32 * max(_nsplit(2, 1, 32, 512 * 8 + r) for r in range(0, 65)) * per_split
 
 
 def test_options(lib):
     tf.tf_set_option("attn_full_tokens_per_split", 256)
     small = tf.tf_decode_attn_full_workspace_bytes(1, 1, 4096, 4)
+    plan = tf.tf_decode_attn_plan(0, 1, 1, 4096)
     tf.tf_set_option("attn_full_tokens_per_split", 0)
-    assert small == 16 * (8 * 128 + 16) * 4
+    assert small == 16 * (8 * 128 + 16) * 4 and plan == (16, 256)
     with pytest.raises(tf.TfError):
         tf.tf_set_option("attn_full_tokens_per_split", 100)      # not a multiple of 64
     with pytest.raises(tf.TfError):
         tf.tf_set_option("no_such_option", 1)
+
+
+def test_thread_options_are_private_to_their_thread(lib):
+    """A knob set with tf_set_thread_option is seen by the setting thread only; other threads keep
+    the process-wide value; -1 removes the override."""
+    import threading
+    seen = {}
+
+    def worker(name, tps):
+        if tps is not None:
+            tf.tf_set_thread_option("attn_full_tokens_per_split", tps)
+        barrier.wait(timeout=30)                    # all overrides are in place before anyone plans
+        seen[name] = tf.tf_decode_attn_plan(0, 1, 1, 8192)
+        if tps is not None:
+            tf.tf_set_thread_option("attn_full_tokens_per_split", -1)
+            seen[name + "_after"] = tf.tf_decode_attn_plan(0, 1, 1, 8192)
+
+    barrier = threading.Barrier(3)
+    auto = tf.tf_decode_attn_plan(0, 1, 1, 8192)
+    ts = [threading.Thread(target=worker, args=a) for a in (("a", 256), ("b", 1024), ("c", None))]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert seen["a"] == (32, 256) and seen["b"] == (8, 1024) and seen["c"] == auto
+    assert seen["a_after"] == auto and seen["b_after"] == auto
+    assert tf.tf_decode_attn_plan(0, 1, 1, 8192) == auto
+    with pytest.raises(tf.TfError):
+        tf.tf_set_thread_option("attn_full_tokens_per_split", 100)
 
 
 def test_host_side_argument_checks(lib):

@@ -110,6 +110,10 @@ PY_MISTAKES = [
      "ctx = np.arange(max(n - G, 0))", "ctx = np.arange(max(n - G + 1, 0))"),
     ("bf16 rounding: one bit too coarse", "test_oracle_retrieval.py", "tf_oracle.py",
      "return np.ldexp(np.rint(m * 256.0), e - 8)", "return np.ldexp(np.rint(m * 128.0), e - 7)"),
+    ("bf16 table: exact mean rounded once instead of the fp32 mean", "test_oracle_retrieval.py", "tf_oracle.py",
+     "return round_to_bf16(chunk_mean_fp32(K, c).astype(np.float64))", "return round_to_bf16(chunk_mean(K, c))"),
+    ("bf16 table: fp32 additions not in token order", "test_oracle_retrieval.py", "tf_oracle.py",
+     "for i in range(c):                          # one rounded", "for i in range(c - 1, -1, -1):               # one rounded"),
     ("ragged accept: every sequence takes the full draft length", "test_oracle_accept.py", "tf_oracle.py",
      "g = int(min(max(int(n_draft[b]), 0), G - 1))", "g = G - 1"),
     ("Algorithm 1: verification against the small model's distribution", "test_oracle_loop.py", "triforce_loop.py",

@@ -164,7 +164,7 @@ def test_full_budget_retrieval_attention_equals_full_attention(c):
 
 
 def test_round_to_bf16_matches_a_library_conversion():
-    """The bf16 average-key variant rounds the exact mean once to bf16. The rounding helper is
+    """The bf16 average-key variant rounds the fp32 chunk mean to bf16. The rounding helper is
     pinned against torch's float32 -> bfloat16 conversion (round to nearest even) on values that
     are exact in float32, and on hand-made ties."""
     import torch
@@ -181,3 +181,59 @@ def test_round_to_bf16_matches_a_library_conversion():
     # the table itself: a chunk of identical keys keeps that key; c = 1 reproduces K
     K = bf16_u16(rng.standard_normal((1, 2, 16, 128)))
     assert np.array_equal(oracle.chunk_mean_bf16(K, 1), u16_f64(K))
+
+
+def test_bf16_table_definition_two_roundings_by_hand():
+    """The bf16 table is defined as: fp32 sequential sum in token order, one fp32 division, then
+    round-to-nearest-even to bf16. Hand-worked chunk (c = 4) on which this differs from the exact
+    mean rounded once: keys 4, 12/256, -2^-30, 0. fp32: 4 + 0.046875 = 4.046875 (exact);
+    adding -2^-30 rounds back to 4.046875 (fp32 spacing at 4 is 2^-21); / 4 = 1 + 3*2^-8, exactly
+    halfway between the bf16 neighbours 1 + 2^-7 and 1 + 2^-6 -> even -> 1 + 2^-6. The exact mean
+    is 1 + 3*2^-8 - 2^-32, just below the halfway point -> 1 + 2^-7 when rounded once."""
+    vals = [4.0, 12.0 / 256.0, -2.0 ** -30, 0.0]
+    K = np.zeros((1, 1, 8, D), dtype=np.float64)
+    K[0, 0, :4, :] = np.array(vals)[:, None]
+    K[0, 0, 4:, 0] = [1.0, 2.0, 3.0, 4.0]               # a second, ordinary chunk: mean 2.5
+    Ku = bf16_u16(K)
+    assert np.array_equal(u16_f64(Ku), K)               # every value is a bf16 value
+    f32 = oracle.chunk_mean_fp32(Ku, 4)
+    assert f32.dtype == np.float32 and f32[0, 0, 0, 5] == np.float32(1 + 3 * 2.0 ** -8)
+    tab = oracle.chunk_mean_bf16(Ku, 4)
+    assert tab[0, 0, 0, 7] == 1 + 2.0 ** -6
+    assert oracle.chunk_mean_bf16_once(Ku, 4)[0, 0, 0, 7] == 1 + 2.0 ** -7
+    assert tab[0, 0, 1, 0] == 2.5 and tab[0, 0, 1, 1] == 0.0
+
+
+def test_bf16_table_order_of_the_fp32_additions():
+    """Token order matters in fp32: 2^24 + 1 + 1 + ... added front to back loses every 1, added
+    back to front it does not. Keys (c = 4): 2^24, 1, 1, 1 -> sequential fp32 sum 2^24 (each +1 is
+    a tie that rounds to the even neighbour 2^24), mean 2^22; the reverse order adds 1 + 1 + 1 = 3
+    first, and 3 + 2^24 rounds to 2^24 + 4: mean 2^22 + 1."""
+    K = np.zeros((1, 1, 8, D))
+    K[0, 0, :4, :] = np.array([2.0 ** 24, 1.0, 1.0, 1.0])[:, None]
+    K[0, 0, 4:, :] = np.array([1.0, 1.0, 1.0, 2.0 ** 24])[:, None]
+    f32 = oracle.chunk_mean_fp32(bf16_u16(K), 4)
+    assert f32[0, 0, 0, 3] == np.float32(2.0 ** 22)
+    assert f32[0, 0, 1, 3] == np.float32(2.0 ** 22 + 1)
+
+
+def test_bf16_table_against_the_exact_mean():
+    """Away from rounding boundaries the definition agrees with the exact mean: the fp32 mean is
+    within (c+1) 2^-24 relative of the fp64 mean (c-1 additions and one division, half an ulp
+    each), the table is the fp64 mean rounded once except for rare boundary cases, which differ by
+    exactly one bf16 ulp; power-of-two chunks of identical keys return that key."""
+    rng = np.random.default_rng(77)
+    for c in (1, 3, 8, 12, 16):
+        K = _rand_u16(rng, (2, 3, 50 * c + c // 2, D))   # ragged tail never summarised
+        exact = oracle.chunk_mean(K, c)
+        f32 = oracle.chunk_mean_fp32(K, c).astype(np.float64)
+        amax = np.abs(u16_f64(K)[:, :, :50 * c].reshape(2, 3, 50, c, D)).max(axis=3)
+        assert np.all(np.abs(f32 - exact) <= (c + 1) * 2.0 ** -24 * np.maximum(amax, np.abs(exact)))
+        two, once = oracle.chunk_mean_bf16(K, c), oracle.chunk_mean_bf16_once(K, c)
+        diff = two != once
+        assert diff.mean() < 1e-3
+        if diff.any():
+            ulp = 2.0 ** (np.floor(np.log2(np.abs(once[diff]))) - 7)
+            assert np.all(np.abs(two[diff] - once[diff]) <= ulp * 1.0000001)
+    K = np.repeat(_rand_u16(rng, (1, 2, 5, 1, D)), 8, axis=3).reshape(1, 2, 40, D)
+    assert np.array_equal(oracle.chunk_mean_bf16(K, 8), u16_f64(K[:, :, ::8]))
