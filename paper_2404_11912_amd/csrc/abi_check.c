@@ -189,7 +189,9 @@ int main(void)
            TF_ERR_INVALID_ARG);
     EXPECT(tf_chunk_summarize(dK, &kd, C, 0, M + 1, (float *)dM, M, NULL) == TF_ERR_INVALID_ARG);
     EXPECT(tf_chunk_topk_gather(dq, (const float *)dM, M, dK, dV, &kd, C, NULL, M, TF_MAX_K_CHUNKS + 1, (int32_t *)dIdx,
-                                NULL, dKr, dVr, &rd, ws, ws_bytes, NULL) == TF_ERR_UNSUPPORTED);
+                                NULL, NULL, NULL, NULL, ws, ws_bytes, NULL) == TF_ERR_UNSUPPORTED);
+    EXPECT(tf_chunk_topk_gather(dq, (const float *)dM, M, dK, dV, &kd, C, NULL, M, KSEL + 1, (int32_t *)dIdx,
+                                NULL, dKr, dVr, &rd, ws, ws_bytes, NULL) == TF_ERR_INVALID_ARG);   /* cache too small */
     EXPECT(tf_decode_attn_retrieval(dQ, dKr, dVr, &rd, NULL, R, G, 0.0f, 1, (float *)dO, (float *)dL, ws, 16, NULL) ==
            TF_ERR_WORKSPACE);
 
