@@ -60,6 +60,8 @@ extern "C" {
 #define TF_ERR_UNSUPPORTED (-2) /* head_dim not supported, G > 16, k_chunks > 2048, ...       */
 #define TF_ERR_WORKSPACE (-3)   /* workspace missing, misaligned or too small                */
 #define TF_ERR_HIP (-4)         /* a HIP runtime call (kernel launch) reported an error      */
+#define TF_ERR_SCRATCH_LIMIT (-5) /* tf_decode_attn_retrieval_noalloc: the problem needs more
+                                     scratch than the library's built-in buffer holds          */
 
 #define TF_HEAD_DIM 128
 #define TF_MAX_QUERIES 16    /* G = gamma + 1 queries (or tree nodes) per attention call      */
@@ -226,6 +228,30 @@ int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const 
                              const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
                              int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes,
                              void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * tf_decode_attn_retrieval_noalloc -- for callers that cannot allocate or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. The same operation,
+ * kernels, launch shape and results (bit for bit) as tf_decode_attn_retrieval, but the split partials
+ * live in a buffer built into the library (a file-scope device array of tf_noalloc_scratch_bytes() =
+ * 8 MiB that every GPU the library runs on holds until the process ends) instead of a workspace
+ * argument. Neither this call nor tf_noalloc_init allocates or frees memory.
+ *   - Limit: the call needs what tf_decode_attn_retrieval_workspace_bytes(batch, heads, kv_len_all,
+ *     G * q_group) reports; beyond tf_noalloc_scratch_bytes() it returns TF_ERR_SCRATCH_LIMIT and
+ *     enqueues nothing (8 MiB hold e.g. 32 heads x 64 splits, far more than a 4K..16K budget plans).
+ *   - All calls on one GPU share that GPU's buffer: calls that may overlap on one GPU (different
+ *     streams, or two captured graphs replayed concurrently) race on it and must be ordered by the
+ *     caller. Nothing in the buffer has to be cleared between calls: every partial a call's merge
+ *     step reads was written by that call's split step.
+ *   - The buffer's device address is looked up on the first call on each device (with that device
+ *     current); tf_noalloc_init() does the same lookup ahead of time for the current device, e.g.
+ *     before a graph capture begins. Returns TF_ERR_HIP if the lookup fails.
+ * ------------------------------------------------------------------------------------- */
+int tf_noalloc_init(void);
+size_t tf_noalloc_scratch_bytes(void);
+int tf_decode_attn_retrieval_noalloc(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                                     const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
+                                     int32_t causal, float *O, float *LSE, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * tf_decode_attn_indexed -- gather-free drafting (Algorithm 1, the pass of M_p over the retrieval

@@ -28,6 +28,9 @@ from .binding import (  # noqa: F401
     tf_decode_attn_full_workspace_bytes,
     tf_decode_attn_retrieval,
     tf_decode_attn_retrieval_workspace_bytes,
+    tf_decode_attn_retrieval_noalloc,
+    tf_noalloc_init,
+    tf_noalloc_scratch_bytes,
     tf_set_option,
     tf_set_thread_option,
     tf_spec_accept,

@@ -21,6 +21,7 @@ TF_MAX_SPEC = 16
 
 EXPORTS = (
     "tf_version", "tf_status_string", "tf_set_option", "tf_set_thread_option", "tf_decode_attn_plan",
+    "tf_noalloc_init", "tf_noalloc_scratch_bytes", "tf_decode_attn_retrieval_noalloc",
     "tf_chunk_summarize",
     "tf_chunk_topk_gather_workspace_bytes", "tf_chunk_topk_gather",
     "tf_decode_attn_full_workspace_bytes", "tf_decode_attn_full",
@@ -83,6 +84,12 @@ def load_library() -> ctypes.CDLL:
         getattr(lib, name + "_workspace_bytes").argtypes = [i32, i32, i64, i32]
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, i32, vp, vp, vp, sz, vp]
+    lib.tf_noalloc_init.restype = ctypes.c_int
+    lib.tf_noalloc_init.argtypes = []
+    lib.tf_noalloc_scratch_bytes.restype = sz
+    lib.tf_noalloc_scratch_bytes.argtypes = []
+    lib.tf_decode_attn_retrieval_noalloc.restype = ctypes.c_int
+    lib.tf_decode_attn_retrieval_noalloc.argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, i32, vp, vp, vp]
     lib.tf_decode_attn_plan.restype = ctypes.c_int
     lib.tf_decode_attn_plan.argtypes = [i32, i32, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.tf_decode_attn_indexed_workspace_bytes.restype = sz
@@ -273,6 +280,11 @@ def _attn(name, Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream, 
             raise ValueError("kv_len must be [B]")
     if kv_len_all is None:
         kv_len_all = K.shape[2]
+    if name == "tf_decode_attn_retrieval_noalloc":        # no workspace argument: the library's own buffer
+        _check(name, getattr(lib, name)(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(kv_len), int(kv_len_all),
+                                        int(G), float(scale), int(bool(causal)), _ptr(O), _ptr(LSE),
+                                        _stream(stream)))
+        return O
     if ws is None:
         ws_name = "tf_decode_attn_full" if tail_mask is not None else name
         nbytes = getattr(lib, ws_name + "_workspace_bytes")(d.batch, d.heads, int(kv_len_all), int(G) * d.q_group)
@@ -325,6 +337,23 @@ def tf_decode_attn_retrieval(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None,
                              causal: bool = True, ws=None, stream=None):
     """Draft attention: the same operation over the retrieval cache (K, V = Kr, Vr)."""
     return _attn("tf_decode_attn_retrieval", Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream)
+
+
+def tf_noalloc_init() -> None:
+    """Look up the built-in scratch buffer of the current device (no allocation)."""
+    _check("tf_noalloc_init", load_library().tf_noalloc_init())
+
+
+def tf_noalloc_scratch_bytes() -> int:
+    return int(load_library().tf_noalloc_scratch_bytes())
+
+
+def tf_decode_attn_retrieval_noalloc(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None, scale: float = 1.0,
+                                     causal: bool = True, stream=None):
+    """tf_decode_attn_retrieval with the library's built-in scratch buffer: no workspace argument and
+    no allocation anywhere on the way (this wrapper allocates nothing either)."""
+    return _attn("tf_decode_attn_retrieval_noalloc", Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, None,
+                 stream)
 
 
 def tf_decode_attn_indexed_workspace_bytes(batch: int, heads: int, k_chunks: int, chunk: int,

@@ -16,6 +16,10 @@ int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, co
                 float, int32_t, float *, float *, void *, size_t, void *, bool, const IndexedArgs *, const uint16_t *);
 int kv_append_launch(const void *, const void *, int32_t, void *, void *, const tf_kv_desc *, const int32_t *,
                      int64_t, void *);
+int attn_noalloc_init();
+size_t attn_noalloc_max_bytes();
+int attn_retrieval_noalloc_launch(const void *, const void *, const void *, const tf_kv_desc *, const int32_t *, int64_t,
+                                  int32_t, float, int32_t, float *, float *, void *);
 int attn_plan(int32_t, int32_t, int32_t, int64_t, int32_t *, int32_t *);
 int set_attn_option(bool retrieval, int64_t v, bool this_thread);
 int set_score_option(int64_t v, bool this_thread);
@@ -35,6 +39,7 @@ const char *tf_status_string(int code) {
         case TF_ERR_UNSUPPORTED: return "unsupported shape or size";
         case TF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case TF_ERR_HIP: return "HIP runtime error";
+        case TF_ERR_SCRATCH_LIMIT: return "problem needs more than the library's built-in scratch buffer";
         default: return "unknown status";
     }
 }
@@ -112,6 +117,16 @@ int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const 
                              const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale, int32_t causal,
                              float *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
     return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, true, nullptr, nullptr);
+}
+
+int tf_noalloc_init(void) { return tf::attn_noalloc_init(); }
+
+size_t tf_noalloc_scratch_bytes(void) { return tf::attn_noalloc_max_bytes(); }
+
+int tf_decode_attn_retrieval_noalloc(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                                     const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
+                                     int32_t causal, float *O, float *LSE, void *stream) {
+    return tf::attn_retrieval_noalloc_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, stream);
 }
 
 size_t tf_decode_attn_indexed_workspace_bytes(int32_t batch, int32_t heads, int32_t k_chunks, int32_t chunk,

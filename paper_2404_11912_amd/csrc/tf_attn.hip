@@ -679,4 +679,51 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     return hip_status(hipGetLastError());
 }
 
+// ---- the entry point that allocates nothing ---------------------------------------------------
+// For callers that cannot allocate (HIP graph capture, tight serving loops): the split partials of
+// the draft attention live in a file-scope device array instead of a caller workspace. Every GPU
+// holds its own copy of the array at its own address; the address is looked up once per device
+// (with that device current) and only that pointer is ever handed to kernels. The array's name in
+// host code is a stand-in for the symbol, not a device address.
+constexpr size_t kScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
+constexpr int kScratchMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kScratchMaxDevices];  // zero-initialised: not looked up yet
+
+static int scratch_of_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kScratchMaxDevices) return TF_ERR_HIP;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TF_ERR_HIP;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // racing threads store the same address
+    }
+    *out = ptr;
+    return TF_OK;
+}
+
+int attn_noalloc_init() {
+    void *ptr = nullptr;
+    return scratch_of_current_device(&ptr);
+}
+
+size_t attn_noalloc_max_bytes() { return kScratchBytes; }
+
+int attn_retrieval_noalloc_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
+                                  const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale, int32_t causal,
+                                  float *O, float *LSE, void *stream) {
+    // the size check comes first and touches no device: a too-large problem is refused the same way
+    // whether or not the scratch address has been looked up yet
+    if (kd && kd->batch > 0 && kd->heads > 0 && kv_len_all > 0 && G > 0) {
+        const int q_group = kd->q_group > 0 ? kd->q_group : 1;
+        const size_t need = attn_workspace_bytes(kd->batch, kd->heads, kv_len_all, G * q_group, true);
+        if (need > kScratchBytes) return TF_ERR_SCRATCH_LIMIT;
+    }
+    void *ptr = nullptr;
+    const int rc = scratch_of_current_device(&ptr);
+    if (rc != TF_OK) return rc;
+    return attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ptr, kScratchBytes, stream, true,
+                       nullptr, nullptr);
+}
+
 }  // namespace tf
