@@ -234,11 +234,13 @@ int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const 
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. The same operation,
  * kernels, launch shape and results (bit for bit) as tf_decode_attn_retrieval, but the split partials
  * live in a buffer built into the library (a file-scope device array of tf_noalloc_scratch_bytes() =
- * 8 MiB that every GPU the library runs on holds until the process ends) instead of a workspace
+ * 16 MiB that every GPU the library runs on holds until the process ends) instead of a workspace
  * argument. Neither this call nor tf_noalloc_init allocates or frees memory.
- *   - Limit: the call needs what tf_decode_attn_retrieval_workspace_bytes(batch, heads, kv_len_all,
- *     G * q_group) reports; beyond tf_noalloc_scratch_bytes() it returns TF_ERR_SCRATCH_LIMIT and
- *     enqueues nothing (8 MiB hold e.g. 32 heads x 64 splits, far more than a 4K..16K budget plans).
+ *   - Limit: the partials of the launch shape the call plans must fit the buffer:
+ *     batch * heads * nsplit * 4 * rows * 130 * 4 bytes, nsplit as tf_decode_attn_plan(TF_PLAN_RETRIEVAL,
+ *     ...) reports, rows = 8 (16 when G * q_group > 8). Beyond tf_noalloc_scratch_bytes() the call
+ *     returns TF_ERR_SCRATCH_LIMIT and enqueues nothing. (16 MiB hold e.g. 32 heads x 30 splits, while
+ *     a 4K..16K budget plans 8.)
  *   - All calls on one GPU share that GPU's buffer: calls that may overlap on one GPU (different
  *     streams, or two captured graphs replayed concurrently) race on it and must be ordered by the
  *     caller. Nothing in the buffer has to be cleared between calls: every partial a call's merge

@@ -8,20 +8,24 @@
 // `nsplit` contiguous ranges, one 256-thread workgroup each; its 4 waves walk interleaved
 // 16-token tiles, so the workgroup streams K and V front to back. Per tile and wave:
 //   * K rows arrive as MFMA A-operands (lane (r,s): token r, dims 32kk+8s..+8) and four
-//     v_mfma_f32_16x16x32_bf16 give S^T[token, query] against the Q operand, which lives in
-//     LDS and is re-read per tile (16 VGPRs fewer);
-//   * the accumulator layout (lane (r,s), reg i = token 4s+i, query r) is exactly the
-//     A-operand layout of v_mfma_f32_16x16x4_f32, so P = exp2(S - m) feeds the PV product
-//     with no data movement; V rows arrive fully coalesced (lane (r,s): token 4s+i, dims
+//     v_mfma_f32_16x16x32_bf16 give S^T[token, query] against the Q operand, which every wave
+//     keeps in a private LDS slot and re-reads per tile (16 VGPRs fewer; no workgroup barrier);
+//   * more than 4 query rows: the accumulator layout (lane (r,s), reg i = token 4s+i, query r) is
+//     exactly the A-operand layout of v_mfma_f32_16x16x4_f32, so P = exp2(S - m) feeds the PV
+//     product with no data movement; V rows arrive fully coalesced (lane (r,s): token 4s+i, dims
 //     8r..8r+8), are widened bf16->fp32 in registers and serve as B-operands. P and V stay
 //     fp32, so the only rounding is fp32 accumulation.
+//   * up to 4 query rows (the draft pass): a 16-column MFMA would spend 32 x 32 matrix-pipe cycles
+//     per tile on columns that are mostly zero queries, which is what bounds a short cache; here
+//     every lane multiplies its own 4 tokens x 8 dims of V by the probabilities of each query row,
+//     fetched from the lane that holds them by a row broadcast: 32 G FMAs per tile and lane.
 //   * online softmax: the per-query running maximum is reduced over the tile with two
 //     wave shuffles; accumulators are rescaled only when a maximum actually grows.
 //   * all K/V loads carry the nt bit: the cache is touched once per pass and must not displace
 //     anything in L2 / the last-level cache (+15% bandwidth measured).
-// The 4 waves merge (m, l, O) through LDS and write one fp32 partial per split; a small
-// second kernel merges the splits by log-sum-exp and normalises. The host plans the splits so
-// that, where batch x heads allows, exactly one workgroup runs per CU (see plan_splits).
+// Every wave writes its own partial (m, l, O); a small second kernel merges the 4 x nsplit partials of
+// a unit by log-sum-exp and normalises. The host plans the splits so that, where batch x heads
+// allows, exactly one workgroup runs per CU (see plan_splits).
 // The 16 columns of the QK^T MFMA hold up to 16 query rows, so the query heads of a
 // grouped-query KV head share its pass; head dim 128 or 64.
 #include <atomic>
@@ -54,8 +58,8 @@ struct AttnParams {
     uint64_t tail_mask[4];  // 16 rows of 16 bits
     int32_t nsplit, tokens_per_split;
     float scale_log2;
-    float *part_o;   // [BH][nsplit][rows][head dim], rows = 8 or 16 (the kernel's kRows)
-    float *part_ml;  // [BH][nsplit][2][rows]   (running max in log2 units, then sum)
+    float *part_o;   // [BH][nsplit * 4 waves][rows][head dim], rows = 8 or 16 (the kernel's kRows)
+    float *part_ml;  // [BH][nsplit * 4 waves][2][rows]   (running max in log2 units, then sum)
     // indexed mode only: the virtual sequence of (b,h) is the chunks idx[b,h,0..k_chunks) of the
     // cache (chunk j = rows idx*chunk .. idx*chunk+chunk-1, negative entries skipped) followed
     // by the cache rows [recent_begin, len)
@@ -68,9 +72,19 @@ struct AttnParams {
 
 __device__ __forceinline__ float safe_max(float m) { return m == -INFINITY ? 0.0f : m; }
 
+// value of lane kSrc of this lane's row of 16 lanes (DPP row broadcast; no LDS traffic)
+template <int kSrc>
+__device__ __forceinline__ float row_bcast(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + kSrc, 0xf,
+                                                                 0xf, false));
+}
+
+constexpr int kValuRows = 4;  // most query rows the vector-ALU form of the PV product takes
+
 // kD = head dim (128, or 64 for the small draft model's cache): kD/32 K loads and bf16 MFMAs per
-// tile, kD/16 output dims (accumulators) per lane.
-template <bool kIndexed, int kDepth, int kD, int kRows>
+// tile, kD/16 output dims (accumulators) per lane. kValu: at most kValuRows query rows, PV on the
+// vector ALU (see the file comment).
+template <bool kIndexed, int kDepth, int kD, int kRows, bool kValu>
 __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     constexpr int kNK = kD / 32;
     constexpr int kNE = kD / 16;
@@ -121,7 +135,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     // Q operand of the QK^T MFMAs, kept in LDS (re-read per tile: 4 KiB per tile is nothing for
     // LDS, and 16 VGPRs fewer per lane buy a third wave per SIMD): entry [kk][lane] holds
     // Q[query r][32kk + 8s .. +8] for lane (r,s), zero for r >= G
-    __shared__ uint4 sm_q[kNK][kWave];
+    // Every wave keeps a copy of its own: a lane reads back only what it wrote itself, so no
+    // barrier stands between the start of the kernel and the first K/V loads.
+    __shared__ uint4 sm_q[kWaves][kNK][kWave];
     // indexed mode: the chunk indices this split walks, staged once (a global index load in front
     // of every row load would put two memory latencies in series per tile)
     constexpr int kIdxStage = kIndexed ? 1024 : 1;
@@ -132,15 +148,20 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         for (int j = j_first + tid; j < min(j_end, j_first + kIdxStage); j += 256)
             sm_idx[j - j_first] = p.idx[(int64_t)bh * p.k_chunks + j];
     }
-    if (wave == 0) {
+    // The Q loads are requested here, all at once and without a branch (rows past G read row G-1 and
+    // are zeroed on the way to LDS); the LDS write, which has to wait for them, comes after the
+    // first K/V requests are out, so one memory latency covers Q, K and V together.
+    uint4 qv[kNK];
+    {
+        const uint16_t *qp = p.Q + ((int64_t)bh * p.G + min(r, p.G - 1)) * kD + s * 8;
 #pragma unroll
-        for (int kk = 0; kk < kNK; ++kk) {
-            uint4 qv = make_uint4(0, 0, 0, 0);
-            if (r < p.G) qv = ld16(p.Q + ((int64_t)bh * p.G + r) * kD + kk * 32 + s * 8);
-            sm_q[kk][lane] = qv;
-        }
+        for (int kk = 0; kk < kNK; ++kk) qv[kk] = ld16(qp + kk * 32);
     }
-    __syncthreads();
+    auto stage_q = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < kNK; ++kk) sm_q[wave][kk][lane] = r < p.G ? qv[kk] : make_uint4(0, 0, 0, 0);
+    };
+    if constexpr (kIndexed) __syncthreads();  // the staged indices are shared by the workgroup
 
     // tokens < n_all are visible to every query; of the last G tokens this lane's query sees
     // those whose bit is set in my_mask
@@ -150,9 +171,16 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
                                         : (my_row < 12 ? p.tail_mask[2] : p.tail_mask[3]);
     const uint32_t my_mask = (uint32_t)(my_word >> (16 * (my_row & 3))) & 0xffffu;
 
-    f32x4_t o[kNE];
+    // MFMA form: o[e][j] = O[query 4s+j][dim kNE*r+e]; vector-ALU form: ov[g][e] = this lane's share
+    // (its tokens 4s..4s+3 of every tile) of O[query g][dim kNE*r+e]
+    f32x4_t o[kValu ? 1 : kNE];
+    float ov[kValu ? kValuRows : 1][kNE];
 #pragma unroll
-    for (int e = 0; e < kNE; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < (kValu ? 1 : kNE); ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int g = 0; g < (kValu ? kValuRows : 1); ++g)
+#pragma unroll
+        for (int e = 0; e < kNE; ++e) ov[g][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
     // indexed mode: cache row of virtual token v, or -1 if it does not exist
@@ -210,7 +238,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         asm volatile("" ::: "memory");  // keep the Q reads inside the loop (not hoisted into registers)
         uint4 qb[kNK];
 #pragma unroll
-        for (int kk = 0; kk < kNK; ++kk) qb[kk] = sm_q[kk][lane];
+        for (int kk = 0; kk < kNK; ++kk) qb[kk] = sm_q[wave][kk][lane];
 #pragma unroll
         for (int kk = 0; kk < kNK; ++kk)
             sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, k[kk]),
@@ -236,11 +264,20 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some query's maximum grew
             const float alpha = __builtin_amdgcn_exp2f(m_run - safe_max(m_new));
             l_run *= alpha;
+            if constexpr (kValu) {
+                const float a4[kValuRows] = {row_bcast<0>(alpha), row_bcast<1>(alpha), row_bcast<2>(alpha),
+                                             row_bcast<3>(alpha)};  // factor of query g: held by lane g of the row
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float aj = __shfl(alpha, 4 * s + j, kWave);  // factor of query 4s+j
+                for (int g = 0; g < kValuRows; ++g)
 #pragma unroll
-                for (int e = 0; e < kNE; ++e) o[e][j] *= aj;
+                    for (int e = 0; e < kNE; ++e) ov[g][e] *= a4[g];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float aj = __shfl(alpha, 4 * s + j, kWave);  // factor of query 4s+j
+#pragma unroll
+                    for (int e = 0; e < kNE; ++e) o[e][j] *= aj;
+                }
             }
             m_run = m_new;
         }
@@ -252,10 +289,23 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+            if constexpr (kValu) {
+                // pr[i] of lane (g, s) is the weight of token 4s+i for query g: bring it to every
+                // lane of the row, multiply this lane's kNE dims of that token's V row
+                const float pg[kValuRows] = {row_bcast<0>(pr[i]), row_bcast<1>(pr[i]), row_bcast<2>(pr[i]),
+                                             row_bcast<3>(pr[i])};
 #pragma unroll
-            for (int e = 0; e < kNE; ++e) {
-                const float vf = (e & 1) ? bf16hi(w[e >> 1]) : bf16lo(w[e >> 1]);
-                o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[i], vf, o[e], 0, 0, 0);
+                for (int e = 0; e < kNE; ++e) {
+                    const float vf = (e & 1) ? bf16hi(w[e >> 1]) : bf16lo(w[e >> 1]);
+#pragma unroll
+                    for (int g = 0; g < kValuRows; ++g) ov[g][e] = fmaf(pg[g], vf, ov[g][e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < kNE; ++e) {
+                    const float vf = (e & 1) ? bf16hi(w[e >> 1]) : bf16lo(w[e >> 1]);
+                    o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[i], vf, o[e], 0, 0, 0);
+                }
             }
         }
     };
@@ -279,6 +329,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
             load_k(t_first + j * step, j < n_mine_tiles, kb[j], rws[j]);
             vms[j] = load_v(t_first + j * step, j < n_mine_tiles, vb[j], rws[j]);
         }
+        stage_q();
         for (int i = 0; i < n_mine_tiles; i += kDepth) {
 #pragma unroll
             for (int j = 0; j < kDepth; ++j) {
@@ -295,6 +346,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     // plain mode, ragged tail (len not a multiple of 16): one partial tile, rows clamped to the
     // last valid token and masked; handled by the wave whose turn it would be
     if (!kIndexed && t_begin + n_full * kTile < t_end && (n_full % kWaves) == wave) {
+        if (n_mine_tiles <= 0) stage_q();
         const int t0 = t_begin + n_full * kTile;
         uint4 kt[kNK], vt[4];
         float z[4];
@@ -312,54 +364,93 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     l_run += __shfl_xor(l_run, 16, kWave);
     l_run += __shfl_xor(l_run, 32, kWave);
 
-    __shared__ float sm_o[kWaves][kRows][kD];
-    __shared__ float sm_m[kWaves][16];
-    __shared__ float sm_l[kWaves][16];
-    if (s == 0) {
-        sm_m[wave][r] = m_run;
-        sm_l[wave][r] = l_run;
+    // every wave publishes its own partial: no LDS, no barrier; the merge kernel weighs them
+    const int64_t pidx = ((int64_t)bh * p.nsplit + split) * kWaves + wave;
+    float *po = p.part_o + pidx * kRows * kD;
+    if (s == 0 && r < p.G) {
+        p.part_ml[(pidx * 2 + 0) * kRows + r] = m_run;
+        p.part_ml[(pidx * 2 + 1) * kRows + r] = l_run;
     }
-    if (4 * s < kRows) {
+    if constexpr (kValu) {
+        // sum the four token groups (lanes (r, 0..3)), then lanes (r, 0) write dims kNE*r.. of each query
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float *dst = &sm_o[wave][4 * s + j][kNE * r];
-            *reinterpret_cast<float4 *>(dst) = make_float4(o[0][j], o[1][j], o[2][j], o[3][j]);
-            if constexpr (kNE == 8)
-                *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4][j], o[5][j], o[6][j], o[7][j]);
-        }
-    }
-    __syncthreads();
-
-    const int64_t pbase = (int64_t)bh * p.nsplit + split;
-    for (int idx = tid; idx < p.G * kD; idx += 256) {
-        const int g = idx / kD, dim = idx % kD;
-        float mw[kWaves], M = -INFINITY;
+        for (int g = 0; g < kValuRows; ++g)
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            mw[w] = sm_m[w][g];
-            M = fmaxf(M, mw[w]);
-        }
-        const float Ms = safe_max(M);
-        float acc = 0.f, lsum = 0.f;
+            for (int e = 0; e < kNE; ++e) {
+                float t = ov[g][e];
+                t += __shfl_xor(t, 16, kWave);
+                t += __shfl_xor(t, 32, kWave);
+                ov[g][e] = t;
+            }
+        if (s == 0) {
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float a = __builtin_amdgcn_exp2f(mw[w] - Ms);
-            acc += a * sm_o[w][g][dim];
-            lsum += a * sm_l[w][g];
+            for (int g = 0; g < kValuRows; ++g)
+                if (g < p.G) {
+                    float *dst = po + g * kD + kNE * r;
+                    *reinterpret_cast<float4 *>(dst) = make_float4(ov[g][0], ov[g][1], ov[g][2], ov[g][3]);
+                    if constexpr (kNE == 8)
+                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(ov[g][4], ov[g][5], ov[g][6], ov[g][7]);
+                }
         }
-        p.part_o[(pbase * kRows + g) * kD + dim] = acc;
-        if (dim == 0) {
-            p.part_ml[(pbase * 2 + 0) * kRows + g] = M;
-            p.part_ml[(pbase * 2 + 1) * kRows + g] = lsum;
-        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (4 * s + j < p.G) {
+                float *dst = po + (4 * s + j) * kD + kNE * r;
+                *reinterpret_cast<float4 *>(dst) = make_float4(o[0][j], o[1][j], o[2][j], o[3][j]);
+                if constexpr (kNE == 8)
+                    *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4][j], o[5][j], o[6][j], o[7][j]);
+            }
     }
 }
 
-// Merge the split partials of one (b,h,g). 512 threads = 4 groups x 128 output dims. The
-// per-split maxima and sums are staged in LDS, turned into weights once, and each group
-// accumulates every 4th split with independent loads in flight; groups are summed in LDS.
+// Merge of few partials (at most kP, a template constant), one 128- or 64-thread workgroup per
+// (b,h,g), thread = output dim. No LDS and no barrier: the maxima and sums of the partials are read
+// with wave-uniform addresses, the kP partial values of this thread's dim are all requested before
+// the first is used, so the whole merge costs about one memory round trip.
+template <int kD, int kP>
+__global__ __launch_bounds__(kD) void attn_combine_small_kernel(const float *__restrict__ part_o,
+                                                                const float *__restrict__ part_ml, int nparts,
+                                                                int G, int rows, float *__restrict__ O,
+                                                                float *__restrict__ LSE) {
+    const int dim = threadIdx.x;
+    const int bh = blockIdx.x / G, g = blockIdx.x - bh * G;
+    const int64_t base = (int64_t)bh * nparts;
+    const float *po = part_o + (base * rows + g) * kD + dim;
+    const float *pm = part_ml + base * 2 * rows + g;
+    const int64_t stride_o = (int64_t)rows * kD, stride_ml = 2 * rows;
+    float ov[kP], mv[kP], lv[kP];
+#pragma unroll
+    for (int sp = 0; sp < kP; ++sp) {
+        const int q = sp < nparts ? sp : 0;        // past the end: partial 0 again, weight 0 below
+        ov[sp] = po[q * stride_o];
+        mv[sp] = sp < nparts ? pm[q * stride_ml] : -INFINITY;
+        lv[sp] = pm[q * stride_ml + rows];
+    }
+    float M = -INFINITY;
+#pragma unroll
+    for (int sp = 0; sp < kP; ++sp) M = fmaxf(M, mv[sp]);
+    const float Ms = safe_max(M);
+    float L = 0.f, acc = 0.f;
+#pragma unroll
+    for (int sp = 0; sp < kP; ++sp) {
+        const float a = __builtin_amdgcn_exp2f(mv[sp] - Ms);   // exp2(-inf) = 0 for empty and padded partials
+        L = fmaf(a, lv[sp], L);
+        acc = fmaf(a, ov[sp], acc);
+    }
+    const int64_t row = (int64_t)bh * G + g;
+    O[row * kD + dim] = L > 0.f ? acc / L : 0.f;
+    if (LSE && dim == 0) LSE[row] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+}
+
+// Merge of many partials of one (b,h,g) (`nsplit` below counts partials: 4 per split). 512 threads
+// = 4 groups x 128 output dims. The per-partial maxima and sums are staged in LDS, turned into
+// weights once, and each group accumulates every 4th partial with independent loads in flight;
+// groups are summed in LDS.
 constexpr int kCombineThreads = 512;
-constexpr int kMaxSplits = 2048;
+constexpr int kMaxParts = 2048;               // partials the merge kernel stages weights for
+constexpr int kMaxSplits = kMaxParts / kWaves;
+constexpr int kSmallParts = 32;               // up to here the barrier-free merge is used (more would spill scalar registers)
 
 template <int kD>
 __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const float *__restrict__ part_o,
@@ -367,8 +458,8 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine_kernel(const flo
                                                                        int nsplit, int G, int rows,
                                                                        float *__restrict__ O,
                                                                        float *__restrict__ LSE) {
-    __shared__ float sm_w[kMaxSplits];   // running max, then weight exp2(m - M), per split
-    __shared__ float sm_l[kMaxSplits];
+    __shared__ float sm_w[kMaxParts];   // running max, then weight exp2(m - M), per partial
+    __shared__ float sm_l[kMaxParts];
     __shared__ float sm_red[kCombineThreads / 64];
     constexpr int kCombineGroups = kCombineThreads / kD;
     __shared__ float sm_acc[kCombineGroups][kD];
@@ -511,7 +602,9 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
             if (ns_cap < 1) ns_cap = 1;
             double best = 0.0;
             for (int64_t ns = 1; ns <= ns_cap; ++ns) {
-                const int64_t t = (((kv_len_all + ns - 1) / ns + 63) / 64) * 64;
+                // whole 16-token tiles per split (the 4 waves interleave tiles, so any tile count balances
+                // them to within one tile)
+                const int64_t t = (((kv_len_all + ns - 1) / ns + kTile - 1) / kTile) * kTile;
                 const int64_t n_eff = (kv_len_all + t - 1) / t;
                 const int64_t per_cu = (BH * n_eff + cus - 1) / cus;
                 const double rate = mode == kPlanIndexed ? (per_cu <= 1 ? 0.80 : (per_cu == 2 ? 0.95 : 1.0))
@@ -540,8 +633,8 @@ static SplitPlan plan_splits(int64_t BH, int64_t kv_len_all, PlanMode mode) {
 // sized for head dim 128 whatever the call's head dim (the queries do not take it); 8 query rows per
 // KV head, 16 when there are more than 8
 static int rows_of(int G) { return G > 8 ? 16 : 8; }
-static size_t attn_ws_bytes(int64_t BH, int64_t nsplit, int G) {
-    return (size_t)BH * nsplit * (rows_of(G) * kHeadDim + 2 * rows_of(G)) * sizeof(float);
+static size_t attn_ws_bytes(int64_t BH, int64_t nsplit, int G) {  // one partial per wave of every split
+    return (size_t)BH * nsplit * kWaves * (rows_of(G) * kHeadDim + 2 * rows_of(G)) * sizeof(float);
 }
 
 // The most splits any call with a length in [1, len_bound] can plan under the options in force.
@@ -648,7 +741,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     p.scale_log2 = scale * kLog2e;
     p.part_o = static_cast<float *>(ws);
     const int rows = rows_of(GQ);
-    p.part_ml = p.part_o + (size_t)BH * sp.nsplit * rows * kd->head_dim;
+    p.part_ml = p.part_o + (size_t)BH * sp.nsplit * kWaves * rows * kd->head_dim;
     p.idx = ix ? ix->idx : nullptr;
     p.k_chunks = ix ? ix->k_chunks : 0;
     p.chunk = ix ? ix->chunk : 1;
@@ -659,22 +752,35 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(BH * sp.nsplit));
     const dim3 cgrid((unsigned)(BH * GQ));
-    auto launch = [&](auto d_tag, auto rows_tag) {
+    const int nparts = sp.nsplit * kWaves;
+    auto launch = [&](auto d_tag, auto rows_tag, auto valu_tag) {
         constexpr int kD = decltype(d_tag)::value, kRows = decltype(rows_tag)::value;
+        constexpr bool kValu = decltype(valu_tag)::value;
         if (ix)
-            hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth, kD, kRows>), grid, dim3(256), 0, st, p);
+            hipLaunchKernelGGL((attn_split_kernel<true, kPipeDepth, kD, kRows, kValu>), grid, dim3(256), 0, st, p);
         else
-            hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth, kD, kRows>), grid, dim3(256), 0, st, p);
-        hipLaunchKernelGGL((attn_combine_kernel<kD>), cgrid, dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
-                           sp.nsplit, GQ, kRows, O, LSE);
+            hipLaunchKernelGGL((attn_split_kernel<false, kPipeDepth, kD, kRows, kValu>), grid, dim3(256), 0, st, p);
+        if (nparts <= 16)
+            hipLaunchKernelGGL((attn_combine_small_kernel<kD, 16>), cgrid, dim3(kD), 0, st, p.part_o, p.part_ml, nparts,
+                               GQ, kRows, O, LSE);
+        else if (nparts <= kSmallParts)
+            hipLaunchKernelGGL((attn_combine_small_kernel<kD, kSmallParts>), cgrid, dim3(kD), 0, st, p.part_o, p.part_ml,
+                               nparts, GQ, kRows, O, LSE);
+        else
+            hipLaunchKernelGGL((attn_combine_kernel<kD>), cgrid, dim3(kCombineThreads), 0, st, p.part_o, p.part_ml,
+                               nparts, GQ, kRows, O, LSE);
     };
     using std::integral_constant;
+    using std::false_type;
+    using std::true_type;
     if (kd->head_dim == 128) {
-        if (rows == 8) launch(integral_constant<int, 128>{}, integral_constant<int, 8>{});
-        else launch(integral_constant<int, 128>{}, integral_constant<int, 16>{});
+        if (GQ <= kValuRows) launch(integral_constant<int, 128>{}, integral_constant<int, 8>{}, true_type{});
+        else if (rows == 8) launch(integral_constant<int, 128>{}, integral_constant<int, 8>{}, false_type{});
+        else launch(integral_constant<int, 128>{}, integral_constant<int, 16>{}, false_type{});
     } else {
-        if (rows == 8) launch(integral_constant<int, 64>{}, integral_constant<int, 8>{});
-        else launch(integral_constant<int, 64>{}, integral_constant<int, 16>{});
+        if (GQ <= kValuRows) launch(integral_constant<int, 64>{}, integral_constant<int, 8>{}, true_type{});
+        else if (rows == 8) launch(integral_constant<int, 64>{}, integral_constant<int, 8>{}, false_type{});
+        else launch(integral_constant<int, 64>{}, integral_constant<int, 16>{}, false_type{});
     }
     return hip_status(hipGetLastError());
 }
@@ -685,7 +791,7 @@ int attn_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *k
 // holds its own copy of the array at its own address; the address is looked up once per device
 // (with that device current) and only that pointer is ever handed to kernels. The array's name in
 // host code is a stand-in for the symbol, not a device address.
-constexpr size_t kScratchBytes = (size_t)8 << 20;
+constexpr size_t kScratchBytes = (size_t)16 << 20;
 static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
 constexpr int kScratchMaxDevices = 64;
 static std::atomic<void *> g_scratch_ptr[kScratchMaxDevices];  // zero-initialised: not looked up yet
@@ -716,8 +822,11 @@ int attn_retrieval_noalloc_launch(const void *Q, const void *K, const void *V, c
     // whether or not the scratch address has been looked up yet
     if (kd && kd->batch > 0 && kd->heads > 0 && kv_len_all > 0 && G > 0) {
         const int q_group = kd->q_group > 0 ? kd->q_group : 1;
-        const size_t need = attn_workspace_bytes(kd->batch, kd->heads, kv_len_all, G * q_group, true);
-        if (need > kScratchBytes) return TF_ERR_SCRATCH_LIMIT;
+        const int64_t BH = (int64_t)kd->batch * kd->heads;
+        if (kv_len_all <= (int64_t)1 << 30) {  // (longer lengths are refused by the launch below)
+            const size_t need = attn_ws_bytes(BH, plan_splits(BH, kv_len_all, kPlanRetrieval).nsplit, G * q_group);
+            if (need > kScratchBytes) return TF_ERR_SCRATCH_LIMIT;
+        }
     }
     void *ptr = nullptr;
     const int rc = scratch_of_current_device(&ptr);

@@ -68,7 +68,7 @@ def test_split_planning(lib):
     assert _nsplit(full, 1, 1, 3) == 1                              # never more splits than 512-token pieces
     assert _nsplit(full, 1, 4, 4096) == 8
     assert _nsplit(full, 1, 1, 1 << 30) <= 2048                     # the merge kernel's limit
-    assert _nsplit(indexed, 1, 32, 512 * 8 + 3) == 22
+    assert _nsplit(indexed, 1, 32, 512 * 8 + 3) == 24
 
 
 def test_workspace_queries_are_monotone_in_the_length(lib):
@@ -76,7 +76,7 @@ def test_workspace_queries_are_monotone_in_the_length(lib):
     the length (4096 tokens of 32 units plan more splits than 4100); the workspace query sizes for
     the most splits any shorter length could plan, so a workspace queried for a bound serves
     every call below it."""
-    per_split = (8 * 128 + 16) * 4
+    per_split = 4 * (8 * 128 + 16) * 4               # one partial per wave: 8 rows x (128 + 2) floats each
     for kind, query in ((0, tf.tf_decode_attn_full_workspace_bytes), (1, tf.tf_decode_attn_retrieval_workspace_bytes)):
         for BH in (1, 4, 32, 192):
             prev = 0
@@ -94,7 +94,7 @@ def test_options(lib):
     small = tf.tf_decode_attn_full_workspace_bytes(1, 1, 4096, 4)
     plan = tf.tf_decode_attn_plan(0, 1, 1, 4096)
     tf.tf_set_option("attn_full_tokens_per_split", 0)
-    assert small == 16 * (8 * 128 + 16) * 4 and plan == (16, 256)
+    assert small == 16 * 4 * (8 * 128 + 16) * 4 and plan == (16, 256)
     with pytest.raises(tf.TfError):
         tf.tf_set_option("attn_full_tokens_per_split", 100)      # not a multiple of 64
     with pytest.raises(tf.TfError):
