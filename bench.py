@@ -5,8 +5,9 @@
 
 One "step" is one pass of the whole hot path over one batch of synthetic input, in the order
 of Algorithm 1 of the paper:
-  1. draft attention over the retrieval cache, layer by layer (tf_decode_attn_retrieval), then
-     the draft-level accept call (tf_spec_accept);
+  1. draft attention over the retrieval cache, layer by layer (tf_decode_attn_retrieval; the
+     G_d tokens in flight are staged behind the budget, rows [R, R+G_d), and the bottom-right
+     causal mask applies to them), then the draft-level accept call (tf_spec_accept);
   2. verification attention over the full cache, layer by layer (tf_decode_attn_full), then
      the verification-level accept call;
   3. the cache update for the next iteration, for all layers at once (the layers are
@@ -17,6 +18,10 @@ The summaries of older chunks do not change between steps (Sec. 3.2, Sec. 4.3: t
 built once after prefill and then updated), so the full-cache summarisation is run and timed
 once before the steps and reported as `one_time` in the JSON line; the retrieval rebuild,
 which the method would amortise over several steps, is paid in every step here.
+Two more step shapes are timed after the headline and reported beside it: `step_alg1_us`, the
+step as Algorithm 1 runs it (ceil(gamma2 / (gamma1 + 1)) draft passes per verification pass, the
+rebuild once every `--rebuild-stride` steps), and `step_gather_free_us`, the headline step with
+the draft pass reading through the chunk indices (tf_decode_attn_indexed) and no gather.
 All inputs are resident in HBM before the timed region. Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -48,6 +53,9 @@ def parse_args():
                     help="also run three plain 1 GiB device copies (a known-size kernel to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
     ap.add_argument("--cpu-sample-layers", type=int, default=4, help="layers in the oracle's timed sample")
+    ap.add_argument("--rebuild-stride", type=int, default=4,
+                    help="steps per retrieval-cache rebuild in the step_alg1_us measurement (the paper gives no "
+                         "value; 4 is the stride the controller tests use)")
     return ap.parse_args()
 
 
@@ -82,8 +90,9 @@ class Step:
             del x
         self.Q_d = self.Q[:, :, -w.G_d:, :].contiguous()
         self.Kmean = torch.empty((LB, H, w.M, d), dtype=torch.float32, device=device)
-        self.Kr = torch.zeros((LB, H, w.R, d), dtype=torch.bfloat16, device=device)
-        self.Vr = torch.zeros((LB, H, w.R, d), dtype=torch.bfloat16, device=device)
+        # retrieval cache: R budget rows, then the G_d rows of the draft pass in flight
+        self.Kr = torch.zeros((LB, H, w.R + w.G_d, d), dtype=torch.bfloat16, device=device)
+        self.Vr = torch.zeros((LB, H, w.R + w.G_d, d), dtype=torch.bfloat16, device=device)
         self.idx = torch.empty((LB, H, w.k), dtype=torch.int32, device=device)
         self.O = torch.empty((LB, H, w.G, d), dtype=torch.float32, device=device)
         self.LSE = torch.empty((LB, H, w.G), dtype=torch.float32, device=device)
@@ -97,8 +106,11 @@ class Step:
         for a, G in ((self.acc_verify, w.G), (self.acc_draft, w.G_d)):
             a["n"] = torch.empty((B,), dtype=torch.int32, device=device)
             a["out"] = torch.empty((B, G), dtype=torch.int32, device=device)
+        # the draft queries' own tokens (here: the newest G_d rows of the full cache) behind the budget
+        tf.tf_kv_append(self.K[:, :, N - w.G_d:].contiguous(), self.V[:, :, N - w.G_d:].contiguous(), self.Kr,
+                        self.Vr, pos_all=w.R)
         nbytes = max(tf.tf_decode_attn_full_workspace_bytes(B, H, N, w.G),
-                     tf.tf_decode_attn_retrieval_workspace_bytes(B, H, w.R, w.G_d),
+                     tf.tf_decode_attn_retrieval_workspace_bytes(B, H, w.R + w.G_d, w.G_d),
                      tf.tf_decode_attn_indexed_workspace_bytes(B, H, w.k, w.c, w.G_d, w.G_d),
                      tf.tf_chunk_topk_gather_workspace_bytes(LB, H, w.M, w.k),
                      tf.tf_spec_accept_workspace_bytes(B, w.G, w.V))
@@ -125,8 +137,14 @@ class Step:
         self.tf.tf_chunk_topk_gather(self.q_r, self.Kmean, self.K, self.V, self.w.c, self.w.k, self.idx,
                                      self.Kr, self.Vr, ws=self.ws)
 
+    def rebuild_no_gather(self):
+        """Scores and selection only: the gather-free draft pass reads through the indices."""
+        self.tf.tf_chunk_topk_gather(self.q_r, self.Kmean, self.K, self.V, self.w.c, self.w.k, self.idx,
+                                     None, None, ws=self.ws)
+
     def draft_attn(self, l):
-        self.tf.tf_decode_attn_retrieval(*self.draft_args[l], scale=1.0, causal=True, ws=self.ws)
+        self.tf.tf_decode_attn_retrieval(*self.draft_args[l], kv_len_all=self.w.R + self.w.G_d, scale=1.0,
+                                         causal=True, ws=self.ws)
 
     def verify_attn(self, l):
         self.tf.tf_decode_attn_full(*self.verify_args[l], scale=1.0, causal=True, ws=self.ws)
@@ -174,6 +192,32 @@ class Step:
         call("spec_accept", self.accept, self.acc_verify)
         call("chunk_summarize(new chunks)", self.summarize_new)
         call("chunk_topk_gather", self.rebuild)
+
+    def run_alg1(self, draft_passes, rebuild_now):
+        """One outer iteration of Algorithm 1: `draft_passes` passes of the target model over the
+        retrieval cache (each followed by the first-level accept), one verification pass + accept,
+        summaries of the new chunks, and the retrieval-cache rebuild when it is due."""
+        for _ in range(draft_passes):
+            for l in range(self.L):
+                self.draft_attn(l)
+            self.accept(self.acc_draft)
+        for l in range(self.L):
+            self.verify_attn(l)
+        self.accept(self.acc_verify)
+        self.summarize_new()
+        if rebuild_now:
+            self.rebuild()
+
+    def run_gather_free(self):
+        """The headline step with the draft pass through the chunk indices and no gathered copy."""
+        for l in range(self.L):
+            self.draft_attn_indexed(l)
+        self.accept(self.acc_draft)
+        for l in range(self.L):
+            self.verify_attn(l)
+        self.accept(self.acc_verify)
+        self.summarize_new()
+        self.rebuild_no_gather()
 
     def breakdown(self, reps=3):
         """Per-call device time (us per step, summed over layers), measured outside the timed region."""
@@ -282,6 +326,35 @@ def main():
     verify_avg_s = float(np.mean(verify_ms)) * 1e-3
     achieved = w.kv_bytes_per_layer() / verify_avg_s / 1e9
     breakdown = step.breakdown()
+
+    def time_steps(fn, n):
+        """Mean device time of n calls of fn(i), between two events on the launch stream."""
+        fn(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    # the step as Algorithm 1 runs it: gamma1 = G_d - 1 tokens drafted per inner pass, gamma2 = gamma
+    # tokens collected per verification, so ceil(gamma2 / (gamma1 + 1)) inner passes when all are accepted
+    # (more when some are rejected); the rebuild every `stride` steps
+    draft_passes = max(1, -(-w.gamma // w.G_d))
+    stride = max(1, args.rebuild_stride)
+    n_alg1 = stride * max(1, min(args.steps, 12) // stride)
+    alg1_us = time_steps(lambda i: step.run_alg1(draft_passes, i % stride == stride - 1), n_alg1)
+    gather_free_us = time_steps(lambda i: step.run_gather_free(), max(1, min(args.steps, 10)))
+    step.rebuild()
+    # the read bandwidth this GPU sustains on a plain stream (2 GiB of the K cache, one workgroup per CU)
+    probe_src = (step.K.view(-1)[: 1 << 30] if step.K.numel() >= (1 << 30)
+                 else torch.empty(1 << 30, dtype=torch.bfloat16, device=dev).zero_())
+    sink = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+    probe_bytes = step.tf.tf_stream_read_probe(probe_src, sink)
+    probe_us = time_steps(lambda i: step.tf.tf_stream_read_probe(probe_src, sink), 10)
+    stream_gbps = probe_bytes / probe_us / 1e3
     # rows beyond the five calls, timed outside the step: gather-free draft pass over all layers
     for l in range(L):
         step.draft_attn_indexed(l)
@@ -348,7 +421,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} L={L} H={w.H} N={w.N} d={w.d} chunk={w.c} budget={w.R} "
-                               f"G={w.G} G_draft={w.G_d} V={w.V} T={step.T}; every step: draft attn, verify attn, "
+                               f"G={w.G} G_draft={w.G_d} V={w.V} T={step.T}; every step: draft attn (kv_len=R+G_draft), verify attn, "
                                f"2x accept, new-chunk summaries, full retrieval rebuild"},
         "kv_gbps_whole_step": round(kv_bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
         "breakdown_us_per_step": breakdown,
@@ -356,6 +429,13 @@ def main():
                      "chunk_summarize_gbps": round(summ_bytes / summarize_all_us / 1e3, 1)},
         "step_us_median": round(float(np.median(step_us)), 1),
         "step_us_min": round(float(np.min(step_us)), 1),
+        "step_alg1_us": round(alg1_us, 1),
+        "step_alg1": f"{draft_passes} draft passes (gamma1={w.G_d - 1}) + accepts per verification pass (gamma2={w.gamma}), "
+                     f"new-chunk summaries every step, full rebuild every {stride} steps; mean of {n_alg1} steps",
+        "step_gather_free_us": round(gather_free_us, 1),
+        "seeds": {"layer": "11912 + 1000*workload_index + 17*layer + 101*b", "workload_index": w.index,
+                  "first_layer": synth.seed_for(w, 0), "accept_verify": synth.seed_for(w, 0) + 7,
+                  "accept_draft": synth.seed_for(w, 0) + 8},
         "extra": {"decode_attn_indexed_us_per_step": round(indexed_us, 1),
                   "decode_attn_tree7_us_per_step": round(tree_us, 1),
                   "chunk_topk_gather_bf16_table_us_per_step": round(rebuild_bf16_us, 1),
@@ -366,7 +446,11 @@ def main():
                      # the counter summary was taken on step128k's launches (2 GiB per launch)
                      "traffic": read_traffic_note() if w.name == "step128k" else None,
                      "algorithmic_bytes_per_launch": w.kv_bytes_per_layer(),
-                     "avg_launch_us": round(verify_avg_s * 1e6, 2), "launches_timed": len(verify_ms) * L},
+                     "avg_launch_us": round(verify_avg_s * 1e6, 2), "launches_timed": len(verify_ms) * L,
+                     # the same GPU's plain streaming-read rate (tf_stream_read_probe over 2 GiB), measured
+                     # in this run, and the verification pass as a fraction of it
+                     "stream_read_ceiling_gbps": round(stream_gbps, 1),
+                     "frac_of_stream_ceiling": round(achieved / stream_gbps, 4)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(step, args.cpu_sample_layers)

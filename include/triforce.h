@@ -91,7 +91,9 @@ const char *tf_status_string(int code); /* static string, never NULL */
 
 /* Tuning knobs. Known names:
  *   "attn_full_tokens_per_split", "attn_retr_tokens_per_split"  (multiples of 64; 0 = auto),
- *   "score_steps_per_wave" (16-chunk steps a wave of the scoring kernel takes; 0 = auto).
+ *   "score_steps_per_wave" (16-chunk steps a wave of the scoring kernel takes; 0 = auto),
+ *   "rebuild_fused" (tf_chunk_topk_gather: 0 = auto, 1 = score and select in one kernel whenever a
+ *   unit has at most 16384 chunks, 2 = never; the results do not depend on it).
  * tf_set_option sets the process-wide default (an atomic: safe to call while other threads run
  * calls, which pick up either the old or the new value). tf_set_thread_option sets an override that
  * only the CALLING host thread's later workspace queries and calls see (value -1 removes it), so
@@ -185,6 +187,17 @@ int tf_decode_attn_full(const void *Q, const void *K, const void *V, const tf_kv
                         const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale,
                         int32_t causal, float *O, float *LSE, void *ws, size_t ws_bytes,
                         void *stream);
+
+/* Measurement aid (not a step of the method): a plain streaming read of `bytes` of device memory
+ * at `buf` -- one workgroup per compute unit, each walking a contiguous range with 16-byte
+ * streaming loads, nothing else -- enqueued on `stream`. Timing it gives the read bandwidth this GPU really
+ * sustains, the ceiling the KV-streaming kernels (Algorithm 1's two attention passes) are compared
+ * with, next to the published peak. Reads whole rounds only: *bytes_read (a HOST integer, written
+ * before return) is the number of bytes the kernel reads, <= bytes. `sink` is device scratch of at
+ * least 4 * 256 * (compute units) bytes (one word per thread is stored). buf must be 16-byte
+ * aligned; TF_ERR_INVALID_ARG if the buffer is too small to give every workgroup 32 KiB. */
+int tf_stream_read_probe(const void *buf, size_t bytes, void *sink, size_t sink_bytes, size_t *bytes_read,
+                         void *stream);
 
 /* The launch shape an attention call would take now (split-K over the KV sequence, Algorithm 1's
  * two attention passes): kind 0 = tf_decode_attn_full / tf_decode_attn_tree, 1 =

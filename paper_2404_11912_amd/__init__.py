@@ -34,6 +34,7 @@ from .binding import (  # noqa: F401
     tf_set_option,
     tf_set_thread_option,
     tf_spec_accept,
+    tf_stream_read_probe,
     tf_spec_accept_workspace_bytes,
     tf_version,
     workspace,

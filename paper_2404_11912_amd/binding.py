@@ -21,7 +21,7 @@ TF_MAX_SPEC = 16
 
 EXPORTS = (
     "tf_version", "tf_status_string", "tf_set_option", "tf_set_thread_option", "tf_decode_attn_plan",
-    "tf_noalloc_init", "tf_noalloc_scratch_bytes", "tf_decode_attn_retrieval_noalloc",
+    "tf_noalloc_init", "tf_noalloc_scratch_bytes", "tf_decode_attn_retrieval_noalloc", "tf_stream_read_probe",
     "tf_chunk_summarize",
     "tf_chunk_topk_gather_workspace_bytes", "tf_chunk_topk_gather",
     "tf_decode_attn_full_workspace_bytes", "tf_decode_attn_full",
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
         getattr(lib, name + "_workspace_bytes").argtypes = [i32, i32, i64, i32]
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = [vp, vp, vp, dp, vp, i64, i32, f32, i32, vp, vp, vp, sz, vp]
+    lib.tf_stream_read_probe.restype = ctypes.c_int
+    lib.tf_stream_read_probe.argtypes = [vp, sz, vp, sz, ctypes.POINTER(sz), vp]
     lib.tf_noalloc_init.restype = ctypes.c_int
     lib.tf_noalloc_init.argtypes = []
     lib.tf_noalloc_scratch_bytes.restype = sz
@@ -337,6 +339,18 @@ def tf_decode_attn_retrieval(Q, K, V, O, LSE=None, kv_len=None, kv_len_all=None,
                              causal: bool = True, ws=None, stream=None):
     """Draft attention: the same operation over the retrieval cache (K, V = Kr, Vr)."""
     return _attn("tf_decode_attn_retrieval", Q, K, V, O, LSE, kv_len, kv_len_all, scale, causal, ws, stream)
+
+
+def tf_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor, stream=None) -> int:
+    """Enqueue a plain streaming read of the whole tensor `buf` (contiguous); returns the bytes the
+    kernel reads. `sink`: device scratch of at least 4 * 256 * (compute units) bytes."""
+    if not (buf.is_cuda and sink.is_cuda and buf.is_contiguous() and sink.is_contiguous()):
+        raise ValueError("buf and sink must be contiguous device tensors")
+    n = ctypes.c_size_t(0)
+    _check("tf_stream_read_probe",
+           load_library().tf_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
+                                               sink.numel() * sink.element_size(), ctypes.byref(n), _stream(stream)))
+    return int(n.value)
 
 
 def tf_noalloc_init() -> None:

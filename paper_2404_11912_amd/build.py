@@ -15,7 +15,7 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(PKG, "libtriforce_hip.so")
 
-SOURCES = ["tf_api.hip", "tf_attn.hip", "tf_summarize.hip", "tf_topk_gather.hip", "tf_accept.hip", "tf_cache.hip"]
+SOURCES = ["tf_api.hip", "tf_attn.hip", "tf_summarize.hip", "tf_topk_gather.hip", "tf_accept.hip", "tf_cache.hip", "tf_probe.hip"]
 
 # packed-fp32 instructions are switched off for all device code of this library
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

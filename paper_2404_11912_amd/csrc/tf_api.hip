@@ -16,6 +16,7 @@ int attn_launch(const void *, const void *, const void *, const tf_kv_desc *, co
                 float, int32_t, float *, float *, void *, size_t, void *, bool, const IndexedArgs *, const uint16_t *);
 int kv_append_launch(const void *, const void *, int32_t, void *, void *, const tf_kv_desc *, const int32_t *,
                      int64_t, void *);
+int stream_read_probe_launch(const void *, size_t, void *, size_t, size_t *, void *);
 int attn_noalloc_init();
 size_t attn_noalloc_max_bytes();
 int attn_retrieval_noalloc_launch(const void *, const void *, const void *, const tf_kv_desc *, const int32_t *, int64_t,
@@ -23,6 +24,7 @@ int attn_retrieval_noalloc_launch(const void *, const void *, const void *, cons
 int attn_plan(int32_t, int32_t, int32_t, int64_t, int32_t *, int32_t *);
 int set_attn_option(bool retrieval, int64_t v, bool this_thread);
 int set_score_option(int64_t v, bool this_thread);
+int set_fused_option(int64_t v, bool this_thread);
 size_t accept_workspace_bytes(int32_t, int32_t, int32_t);
 int accept_launch(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, float, const float *,
                   const float *, int32_t *, int32_t *, void *, size_t, void *, const int32_t *);
@@ -49,6 +51,7 @@ static int set_option(const char *name, int64_t value, bool this_thread) {
     if (!strcmp(name, "attn_full_tokens_per_split")) return tf::set_attn_option(false, value, this_thread);
     if (!strcmp(name, "attn_retr_tokens_per_split")) return tf::set_attn_option(true, value, this_thread);
     if (!strcmp(name, "score_steps_per_wave")) return tf::set_score_option(value, this_thread);
+    if (!strcmp(name, "rebuild_fused")) return tf::set_fused_option(value, this_thread);
     return TF_ERR_INVALID_ARG;
 }
 
@@ -117,6 +120,11 @@ int tf_decode_attn_retrieval(const void *Q, const void *K, const void *V, const 
                              const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale, int32_t causal,
                              float *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
     return tf::attn_launch(Q, K, V, kd, kv_len, kv_len_all, G, scale, causal, O, LSE, ws, ws_bytes, stream, true, nullptr, nullptr);
+}
+
+int tf_stream_read_probe(const void *buf, size_t bytes, void *sink, size_t sink_bytes, size_t *bytes_read,
+                         void *stream) {
+    return tf::stream_read_probe_launch(buf, bytes, sink, sink_bytes, bytes_read, stream);
 }
 
 int tf_noalloc_init(void) { return tf::attn_noalloc_init(); }

@@ -35,8 +35,33 @@ int set_score_option(int64_t v, bool this_thread) {
     else g_score_iters.store(v, std::memory_order_relaxed);
     return TF_OK;
 }
+// fused scoring + selection: 0 = automatic, 1 = whenever the shape allows, 2 = never
+static std::atomic<int64_t> g_fused{0};
+static thread_local int64_t t_fused = -1;
+
+int set_fused_option(int64_t v, bool this_thread) {
+    if (this_thread && v == -1) {
+        t_fused = -1;
+        return TF_OK;
+    }
+    if (v < 0 || v > 2) return TF_ERR_INVALID_ARG;
+    if (this_thread) t_fused = v;
+    else g_fused.store(v, std::memory_order_relaxed);
+    return TF_OK;
+}
+static int64_t fused_option() { return t_fused >= 0 ? t_fused : g_fused.load(std::memory_order_relaxed); }
+
 static int64_t score_iters_option() {
     return t_score_iters >= 0 ? t_score_iters : g_score_iters.load(std::memory_order_relaxed);
+}
+
+// compute units of the current device (256 on a full MI355X; also the assumption without a device)
+static int compute_units() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        return 256;
+    return n;
 }
 
 struct ScoreParams {
@@ -397,6 +422,272 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(const float *_
     }
 }
 
+// ---- fused scoring + selection ------------------------------------------------------------------
+// One 512-thread workgroup per (b,h) streams that unit's average keys (the same loads and the same
+// fp32 arithmetic as the scoring kernels above, so the scores are bit-equal to theirs), keeps the
+// order-preserving keys of all scores in LDS and runs the radix select on them: the scores never
+// travel to HBM and back, and while one workgroup of a compute unit selects, the other one streams.
+// Used when there are enough units to fill the chip that way (see topk_gather_launch) and a unit's
+// keys fit the LDS: up to kFusedMaxChunks chunks, 4 bytes each, plus 8 bytes per kept chunk.
+constexpr int kFusedThreads = 512;
+constexpr int kFusedMaxChunks = 16384;
+
+// LDS position of chunk i's key: one word of padding per 32, so that threads reading contiguous
+// ranges of 4..32 keys each spread over the banks
+__device__ __forceinline__ int key_slot(int i) { return i + (i >> 5); }
+static size_t fused_lds_bytes(int64_t n_all, int k) {
+    const size_t words = (size_t)n_all + (size_t)(n_all >> 5) + 2;                // keys, padded; even count
+    return ((words + 1) & ~(size_t)1) * 4 + (size_t)k * 8;                        // then the winners (8-byte aligned)
+}
+
+__device__ __forceinline__ float key_score(uint32_t key) {  // inverse of score_key
+    return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
+}
+
+struct FusedParams {
+    const uint16_t *q_r;
+    const void *Kmean;
+    int64_t M_cap;
+    const int32_t *n_chunks;
+    int32_t n_all, H, k;
+    int32_t *out_idx;
+    float *out_score;
+};
+
+template <bool kBf16>
+__global__ __launch_bounds__(kFusedThreads) void score_select_kernel(const FusedParams p) {
+    extern __shared__ uint32_t sm_dyn[];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wtot[kFusedThreads / 64];
+    __shared__ uint32_t s_digit, s_remaining;
+    uint32_t *sm_key = sm_dyn;
+    const int key_words = (p.n_all + (p.n_all >> 5) + 2 + 1) & ~1;
+    unsigned long long *cand = reinterpret_cast<unsigned long long *>(sm_dyn + key_words);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int kWavesF = kFusedThreads / 64;
+    const int64_t bh = blockIdx.x;
+    const int b = (int)(bh / p.H);
+    int n = p.n_chunks ? p.n_chunks[b] : p.n_all;
+    n = min(max(n, 0), p.n_all);
+    const int last_row = max(n - 1, 0);
+    const int k = p.k, k_eff = min(k, n);
+
+    // ---- phase 1: stream the table, one key per chunk into LDS ------------------------------
+    // (rows past the sequence's chunk count are clamped to its last row: read, scored, never used)
+    const int steps = (n + 15) / 16;                                   // 16-row steps of this unit
+    if constexpr (!kBf16) {
+        const int e = lane & 7, w = lane >> 3;
+        float q[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint2 u = *reinterpret_cast<const uint2 *>(p.q_r + bh * kHeadDim + 32 * j + 4 * e);
+            q[j][0] = bf16lo(u.x); q[j][1] = bf16hi(u.x); q[j][2] = bf16lo(u.y); q[j][3] = bf16hi(u.y);
+        }
+        const float *base = static_cast<const float *>(p.Kmean) + bh * p.M_cap * kHeadDim + 4 * e;
+        auto load = [&](int m0, float4(&v)[8]) {
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const float *row = base + (int64_t)min(m0 + 8 * rr + w, last_row) * kHeadDim;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[4 * rr + j] = ldf4_stream(row + 32 * j);
+            }
+        };
+        auto finish = [&](int m0, const float4(&v)[8]) {
+            float acc[2];
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                float a = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    a = fmaf(q[j][0], v[4 * rr + j].x, a);
+                    a = fmaf(q[j][1], v[4 * rr + j].y, a);
+                    a = fmaf(q[j][2], v[4 * rr + j].z, a);
+                    a = fmaf(q[j][3], v[4 * rr + j].w, a);
+                }
+                a += __shfl_xor(a, 1, kWave);
+                a += __shfl_xor(a, 2, kWave);
+                a += __shfl_xor(a, 4, kWave);
+                acc[rr] = a;
+            }
+            const int m = m0 + 8 * e + w;                               // lanes e = 0 / 1 keep rows m0 + w / m0 + 8 + w
+            if (e < 2 && m < n) sm_key[key_slot(m)] = score_key(e == 0 ? acc[0] : acc[1]);
+        };
+        float4 va[8], vb[8];
+        int i = wave;                                                   // the waves interleave 16-row steps
+        if (i < steps) load(16 * i, va);
+        for (; i + 2 * kWavesF < steps; i += 2 * kWavesF) {
+            load(16 * (i + kWavesF), vb);
+            finish(16 * i, va);
+            load(16 * (i + 2 * kWavesF), va);
+            finish(16 * (i + kWavesF), vb);
+        }
+        if (i + kWavesF < steps) {
+            load(16 * (i + kWavesF), vb);
+            finish(16 * i, va);
+            finish(16 * (i + kWavesF), vb);
+        } else if (i < steps) {
+            finish(16 * i, va);
+        }
+    } else {
+        const int e = lane & 15, w = lane >> 4;
+        float q[8];
+        {
+            const uint4 u = ld16(p.q_r + bh * kHeadDim + 8 * e);
+            q[0] = bf16lo(u.x); q[1] = bf16hi(u.x); q[2] = bf16lo(u.y); q[3] = bf16hi(u.y);
+            q[4] = bf16lo(u.z); q[5] = bf16hi(u.z); q[6] = bf16lo(u.w); q[7] = bf16hi(u.w);
+        }
+        const uint16_t *base = static_cast<const uint16_t *>(p.Kmean) + bh * p.M_cap * kHeadDim + 8 * e;
+        auto load = [&](int m0, uint4(&v)[4]) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+                v[rr] = ld16_stream(base + (int64_t)min(m0 + 4 * rr + w, last_row) * kHeadDim);
+        };
+        auto finish = [&](int m0, const uint4(&v)[4]) {
+            float mine = 0.f;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                float a = fmaf(q[0], bf16lo(v[rr].x), 0.f);
+                a = fmaf(q[1], bf16hi(v[rr].x), a);
+                a = fmaf(q[2], bf16lo(v[rr].y), a);
+                a = fmaf(q[3], bf16hi(v[rr].y), a);
+                a = fmaf(q[4], bf16lo(v[rr].z), a);
+                a = fmaf(q[5], bf16hi(v[rr].z), a);
+                a = fmaf(q[6], bf16lo(v[rr].w), a);
+                a = fmaf(q[7], bf16hi(v[rr].w), a);
+                a += __shfl_xor(a, 1, kWave);
+                a += __shfl_xor(a, 2, kWave);
+                a += __shfl_xor(a, 4, kWave);
+                a += __shfl_xor(a, 8, kWave);
+                if (e == rr) mine = a;
+            }
+            const int m = m0 + 4 * e + w;                               // lane e < 4 keeps row m0 + 4e + w
+            if (e < 4 && m < n) sm_key[key_slot(m)] = score_key(mine);
+        };
+        uint4 va[4], vb[4];
+        int i = wave;
+        if (i < steps) load(16 * i, va);
+        for (; i + 2 * kWavesF < steps; i += 2 * kWavesF) {
+            load(16 * (i + kWavesF), vb);
+            finish(16 * i, va);
+            load(16 * (i + 2 * kWavesF), va);
+            finish(16 * (i + kWavesF), vb);
+        }
+        if (i + kWavesF < steps) {
+            load(16 * (i + kWavesF), vb);
+            finish(16 * i, va);
+            finish(16 * (i + kWavesF), vb);
+        } else if (i < steps) {
+            finish(16 * i, va);
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: radix select of the k_eff-th largest key (keys read from LDS) --------------
+    uint32_t prefix = 0, mask = 0, remaining = (uint32_t)k_eff;
+    if (k_eff > 0) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            for (int i = tid; i < n; i += kFusedThreads) {              // order does not matter here
+                const uint32_t key = sm_key[key_slot(i)];
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            uint32_t hv = 0, incl = 0;
+            if (tid < 256) {                                            // waves 0..3: suffix sums over the bins
+                hv = hist[tid];
+                incl = hv;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const uint32_t u = __shfl_down(incl, off, kWave);
+                    if (lane + off < 64) incl += u;
+                }
+                if (lane == 0) wtot[wave] = incl;
+            }
+            __syncthreads();
+            if (tid < 256) {
+                uint32_t above = 0;
+                for (int w = wave + 1; w < 4; ++w) above += wtot[w];
+                const uint32_t sfx = incl + above, sfx_excl = sfx - hv;
+                if (sfx >= remaining && sfx_excl < remaining) {
+                    s_digit = (uint32_t)tid;
+                    s_remaining = remaining - sfx_excl;
+                }
+            }
+            __syncthreads();
+            prefix |= s_digit << shift;
+            mask |= 0xffu << shift;
+            remaining = s_remaining;
+            __syncthreads();
+        }
+    }
+    const uint32_t T = prefix;                          // key of the k_eff-th largest
+    const uint32_t n_gt = (uint32_t)k_eff - remaining;  // keys strictly above T (all kept)
+
+    // ---- ordered compaction: thread t owns the contiguous index range [i_lo, i_hi) -------------
+    int per = (n + kFusedThreads - 1) / kFusedThreads;
+    per = (per + 3) & ~3;
+    const int i_lo = min(tid * per, n), i_hi = min(n, i_lo + per);
+    uint32_t c_gt = 0, c_eq = 0;
+    for (int i = i_lo; i < i_hi; ++i) {
+        const uint32_t key = sm_key[key_slot(i)];
+        c_gt += key > T;
+        c_eq += key == T;
+    }
+    auto excl_scan = [&](uint32_t v, uint32_t *total) -> uint32_t {
+        uint32_t incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t u = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += u;
+        }
+        __syncthreads();  // wtot may still be read from the previous use
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesF; ++w) {
+            const uint32_t t = wtot[w];
+            if (w < wave) before += t;
+            all += t;
+        }
+        *total = all;
+        return before + incl - v;
+    };
+    uint32_t tot_gt, tot_eq;
+    uint32_t p_gt = excl_scan(c_gt, &tot_gt);
+    uint32_t p_eq = excl_scan(c_eq, &tot_eq);
+    if (k_eff > 0)
+        for (int i = i_lo; i < i_hi; ++i) {
+            const uint32_t key = sm_key[key_slot(i)];
+            const unsigned long long comp =
+                ((unsigned long long)key << 32) | (unsigned long long)(0xffffffffu - (uint32_t)i);
+            if (key > T) {
+                cand[p_gt++] = comp;
+            } else if (key == T) {
+                if (p_eq < remaining) cand[n_gt + p_eq] = comp;
+                ++p_eq;
+            }
+        }
+    __syncthreads();
+
+    // ---- place of every winner on (key desc, index asc): the number of winners above it ----------
+    for (int j = tid; j < k_eff; j += kFusedThreads) {
+        const unsigned long long mine = cand[j];
+        int above = 0;
+#pragma unroll 8
+        for (int i = 0; i < k_eff; ++i) above += cand[i] > mine;
+        p.out_idx[bh * k + above] = (int32_t)(0xffffffffu - (uint32_t)(mine & 0xffffffffull));
+        if (p.out_score) p.out_score[bh * k + above] = key_score((uint32_t)(mine >> 32));
+    }
+    for (int j = k_eff + tid; j < k; j += kFusedThreads) {  // fewer chunks than k: the rest is empty
+        p.out_idx[bh * k + j] = -1;
+        if (p.out_score) p.out_score[bh * k + j] = -INFINITY;
+    }
+}
+
 struct GatherParams {
     const uint16_t *K, *V;
     uint16_t *Kr, *Vr;
@@ -462,6 +753,41 @@ int topk_gather_launch(const void *q_r, const void *Kmean, int64_t M_cap, const 
     const int64_t BH = (int64_t)kd->batch * kd->heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
+    // Fused scoring + selection when a unit's keys fit the LDS and there are at least two units per
+    // compute unit (one streams while the other selects; with fewer units most of the chip would idle
+    // and the three-kernel path, which spreads one unit over many workgroups, is faster).
+    const int64_t fused_opt = fused_option();
+    bool fused = fused_opt != 2 && n_chunks_all <= kFusedMaxChunks &&
+                 (fused_opt == 1 || BH >= 2 * (int64_t)compute_units());
+    if (fused) {
+        const size_t lds = fused_lds_bytes(n_chunks_all, k_chunks);
+        const void *fn = mean_bf16 ? reinterpret_cast<const void *>(&score_select_kernel<true>)
+                                   : reinterpret_cast<const void *>(&score_select_kernel<false>);
+        // more than 64 KiB of dynamic LDS has to be allowed per kernel; if the runtime refuses, the
+        // three-kernel path below serves the call
+        if (lds > (size_t)64 << 10 &&
+            hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            fused = false;
+        }
+        if (fused) {
+            FusedParams fp;
+            fp.q_r = static_cast<const uint16_t *>(q_r);
+            fp.Kmean = Kmean;
+            fp.M_cap = M_cap;
+            fp.n_chunks = n_chunks;
+            fp.n_all = (int32_t)n_chunks_all;
+            fp.H = kd->heads;
+            fp.k = k_chunks;
+            fp.out_idx = out_idx;
+            fp.out_score = out_score;
+            if (mean_bf16)
+                hipLaunchKernelGGL(score_select_kernel<true>, dim3((unsigned)BH), dim3(kFusedThreads), lds, st, fp);
+            else
+                hipLaunchKernelGGL(score_select_kernel<false>, dim3((unsigned)BH), dim3(kFusedThreads), lds, st, fp);
+        }
+    }
+
     ScoreParams sp;
     sp.q_r = static_cast<const uint16_t *>(q_r);
     sp.Kmean = Kmean;
@@ -479,17 +805,21 @@ int topk_gather_launch(const void *q_r, const void *Kmean, int64_t M_cap, const 
     sp.scores = static_cast<float *>(ws);
     sp.score_stride = score_stride_of(n_chunks_all);
     if (sp.blocks_per_bh * BH >= (int64_t)1 << 31) return TF_ERR_UNSUPPORTED;
-    if (mean_bf16)
-        hipLaunchKernelGGL(chunk_score_bf16_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
-    else
-        hipLaunchKernelGGL(chunk_score_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
+    if (!fused) {
+        if (mean_bf16)
+            hipLaunchKernelGGL(chunk_score_bf16_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
+        else
+            hipLaunchKernelGGL(chunk_score_kernel, dim3((unsigned)(sp.blocks_per_bh * BH)), dim3(256), 0, st, sp);
+    }
 
     auto select = [&](auto keep_tag) {
         hipLaunchKernelGGL((topk_select_kernel<decltype(keep_tag)::value>), dim3((unsigned)BH), dim3(kSelThreads), 0,
                            st, sp.scores, sp.score_stride, n_chunks, (int)n_chunks_all, (int)kd->heads,
                            (int)k_chunks, out_idx, out_score);
     };
-    if (n_chunks_all <= 16 * kSelThreads) select(std::integral_constant<int, 16>{});
+    if (fused) {
+        // idx and scores are already on their way
+    } else if (n_chunks_all <= 16 * kSelThreads) select(std::integral_constant<int, 16>{});
     else if (n_chunks_all <= 32 * kSelThreads) select(std::integral_constant<int, 32>{});
     else select(std::integral_constant<int, 0>{});
 
