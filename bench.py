@@ -53,6 +53,10 @@ def parse_args():
                     help="also run three plain 1 GiB device copies (a known-size kernel to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
     ap.add_argument("--cpu-sample-layers", type=int, default=4, help="layers in the oracle's timed sample")
+    ap.add_argument("--draft-budgets", default="",
+                    help="comma-separated retrieval budgets: time only the draft pass (tf_decode_attn_retrieval over "
+                         "L layers) at each of them and print one JSON line (for kernel traces that separate the "
+                         "fixed cost of a launch from its streaming)")
     ap.add_argument("--rebuild-stride", type=int, default=4,
                     help="steps per retrieval-cache rebuild in the step_alg1_us measurement (the paper gives no "
                          "value; 4 is the stride the controller tests use)")
@@ -265,6 +269,41 @@ def cpu_baseline(step, sample_layers):
                       f"({t_acc * 1e3:.1f} ms); chunk means over the whole cache (no incremental mode)"}
 
 
+def draft_budget_sweep(w, L, budgets, dev, reps=5):
+    """The draft pass alone at several retrieval budgets R: L layers of [B,H,R+G_d,d] caches of their
+    own (so consecutive calls never re-read a cache from the last-level cache), G_d queries, staged
+    tokens behind the budget, bottom-right causal mask. Returns per-call device time."""
+    import paper_2404_11912_amd as tf
+    g = torch.Generator(device=dev)
+    g.manual_seed(11912 + 1000 * w.index + 5)
+    out = []
+    for R in budgets:
+        n = R + w.G_d
+        Kr = torch.randn((L * w.B, w.H, n, w.d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        Vr = torch.randn((L * w.B, w.H, n, w.d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        Q = (torch.randn((w.B, w.H, w.G_d, w.d), generator=g, device=dev, dtype=torch.float32) / w.d ** 0.5).to(
+            torch.bfloat16)
+        O = torch.empty((w.B, w.H, w.G_d, w.d), dtype=torch.float32, device=dev)
+        LSE = torch.empty((w.B, w.H, w.G_d), dtype=torch.float32, device=dev)
+        ws = tf.workspace(tf.tf_decode_attn_retrieval_workspace_bytes(w.B, w.H, n, w.G_d), dev)
+        views = [(Kr[l * w.B:(l + 1) * w.B], Vr[l * w.B:(l + 1) * w.B]) for l in range(L)]
+
+        def one_pass():
+            for Kl, Vl in views:
+                tf.tf_decode_attn_retrieval(Q, Kl, Vl, O, LSE, kv_len_all=n, scale=1.0, causal=True, ws=ws)
+        one_pass()
+        torch.cuda.synchronize()
+        ev = [_timed(one_pass) for _ in range(reps)]
+        torch.cuda.synchronize()
+        us = [a.elapsed_time(b) * 1e3 / L for a, b in ev]
+        nsplit, tps = tf.tf_decode_attn_plan(1, w.B, w.H, n)
+        out.append({"budget": R, "kv_len": n, "bytes_per_call": 2 * w.B * w.H * n * w.d * 2,
+                    "splits_per_head": nsplit, "tokens_per_split": tps, "workgroups": w.B * w.H * nsplit,
+                    "us_per_call_mean": round(float(np.mean(us)), 2), "us_per_call_min": round(float(np.min(us)), 2)})
+        del Kr, Vr, views
+    return out
+
+
 def read_traffic_note():
     """HBM bytes per verification launch from the committed rocprofv3 counter summary, if any
     (a line `traffic_bytes_per_launch: <number>` in profiles/attn_full_step128k_pmc.md)."""
@@ -292,6 +331,12 @@ def main():
     L = args.layers or w.L
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.draft_budgets:
+        budgets = [int(x) for x in args.draft_budgets.split(",") if x]
+        print(json.dumps({"metric": "draft attention (tf_decode_attn_retrieval) per layer call", "unit": "us/call",
+                          "workload": f"{w.name}: B={w.B} H={w.H} G_draft={w.G_d} d={w.d}, {L} layer caches per budget",
+                          "sweep": draft_budget_sweep(w, L, budgets, dev)}), flush=True)
+        return
     t_setup = time.perf_counter()
     step = Step(w, L, dev)
     torch.cuda.synchronize()

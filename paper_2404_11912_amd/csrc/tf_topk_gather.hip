@@ -697,22 +697,36 @@ struct GatherParams {
     int32_t H, k, chunk, jblocks;
 };
 
+// A wave copies kCpw selected chunks: their indices first, then, four rows at a time, the rows of all
+// of them are requested before the first is stored (2 kCpw loads of 16 bytes in flight per lane).
+template <int kCpw>
 __global__ __launch_bounds__(256) void chunk_gather_kernel(const GatherParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = (blockIdx.x % p.jblocks) * 4 + wave;
+    const int j0 = ((blockIdx.x % p.jblocks) * 4 + wave) * kCpw;
     const int64_t bh = blockIdx.x / p.jblocks;
-    if (j >= p.k) return;
-    const int m = p.idx[bh * p.k + j];
-    if (m < 0) return;
+    if (j0 >= p.k) return;
+    int m[kCpw];
+#pragma unroll
+    for (int u = 0; u < kCpw; ++u) m[u] = j0 + u < p.k ? p.idx[bh * p.k + j0 + u] : -1;
     const int b = (int)(bh / p.H), h = (int)(bh - (int64_t)b * p.H);
-    const int64_t src = (int64_t)b * p.sb + (int64_t)h * p.sh + (int64_t)m * p.chunk * p.st + (lane & 15) * 8;
-    const int64_t dst = (int64_t)b * p.rb + (int64_t)h * p.rh + (int64_t)j * p.chunk * p.rt + (lane & 15) * 8;
-#pragma unroll 2
+    const int64_t src0 = (int64_t)b * p.sb + (int64_t)h * p.sh + (lane & 15) * 8;
+    const int64_t dst0 = (int64_t)b * p.rb + (int64_t)h * p.rh + (int64_t)j0 * p.chunk * p.rt + (lane & 15) * 8;
     for (int i = lane >> 4; i < p.chunk; i += 4) {
-        const uint4 kv = ld16_stream(p.K + src + (int64_t)i * p.st);
-        const uint4 vv = ld16_stream(p.V + src + (int64_t)i * p.st);
-        st16_stream(p.Kr + dst + (int64_t)i * p.rt, kv);  // nt stores: 6% faster than plain ones here
-        st16_stream(p.Vr + dst + (int64_t)i * p.rt, vv);
+        uint4 kv[kCpw], vv[kCpw];
+#pragma unroll
+        for (int u = 0; u < kCpw; ++u)
+            if (m[u] >= 0) {
+                const int64_t src = src0 + ((int64_t)m[u] * p.chunk + i) * p.st;
+                kv[u] = ld16_stream(p.K + src);
+                vv[u] = ld16_stream(p.V + src);
+            }
+#pragma unroll
+        for (int u = 0; u < kCpw; ++u)
+            if (m[u] >= 0) {
+                const int64_t dst = dst0 + ((int64_t)u * p.chunk + i) * p.rt;
+                st16_stream(p.Kr + dst, kv[u]);  // nt stores: 6% faster than plain ones here
+                st16_stream(p.Vr + dst, vv[u]);
+            }
     }
 }
 
@@ -839,8 +853,11 @@ int topk_gather_launch(const void *q_r, const void *Kmean, int64_t M_cap, const 
         gp.H = kd->heads;
         gp.k = k_chunks;
         gp.chunk = chunk;
-        gp.jblocks = (k_chunks + 3) / 4;
-        hipLaunchKernelGGL(chunk_gather_kernel, dim3((unsigned)(gp.jblocks * BH)), dim3(256), 0, st, gp);
+        // chunks per wave, measured on the 32-layer rebuild (4 GiB read + written): 1: 5.8-5.9 TB/s, 2: 5.7-5.9,
+        // 4: 5.5, 8: 5.6 -- the copy is bound by the mixed read/write rate of the memory, not by loads in flight
+        constexpr int kCpw = 1;
+        gp.jblocks = (k_chunks + 4 * kCpw - 1) / (4 * kCpw);
+        hipLaunchKernelGGL(chunk_gather_kernel<kCpw>, dim3((unsigned)(gp.jblocks * BH)), dim3(256), 0, st, gp);
     }
     return hip_status(hipGetLastError());
 }
