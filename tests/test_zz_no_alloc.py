@@ -77,3 +77,30 @@ def test_noalloc_entry_point_refuses_sizes_beyond_its_buffer():
     with pytest.raises(tf.TfError) as e:
         tf.tf_decode_attn_retrieval_noalloc(Q, K, K, O)
     assert e.value.code == -5
+
+
+def test_noalloc_entry_point_under_hip_graph_capture():
+    """What the entry point is for: captured into a HIP graph (nothing in it allocates or needs a
+    workspace argument), replayed several times with eager work in between; every replay must equal
+    the eager result of the workspace entry point."""
+    print("case noalloc graph capture: B=1 H=8 N=2051 G=3 seed=19003", flush=True)
+    tf.tf_noalloc_init()                                   # address lookup before the capture begins
+    x, Q, K, V = _inputs(1, 8, 2051, 3, 19003)
+    want_O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
+    want_L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_retrieval(Q, K, V, want_O, want_L, causal=True)
+    O = torch.zeros_like(want_O)
+    L = torch.zeros_like(want_L)
+    tf.tf_decode_attn_retrieval_noalloc(Q, K, V, O, L, causal=True)     # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        tf.tf_decode_attn_retrieval_noalloc(Q, K, V, O, L, causal=True)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        O.zero_()
+        L.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, want_O) and torch.equal(L, want_L), f"replay {rep}"
