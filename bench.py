@@ -32,6 +32,11 @@ import os
 import sys
 import time
 
+# Kernel arguments in device memory instead of host memory (a HIP runtime setting, read when the runtime
+# starts): every kernel begins by reading its arguments, and the short launches of this path (draft pass,
+# merge, accept) measured 0.5 - 0.9 us shorter each with it. Set it to 0 in the environment to compare.
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+
 import numpy as np
 import torch
 
