@@ -49,6 +49,15 @@ def test_one_layer_at_full_size(name, layer):
     O = torch.empty(Q.shape, dtype=torch.float32, device=DEV)
     L = torch.empty(Q.shape[:3], dtype=torch.float32, device=DEV)
     tf.tf_decode_attn_full(Q, K, V, O, L, causal=True)
+    # the draft pass as the benchmark step runs it: the G_d tokens in flight staged behind the budget
+    # (rows [R, R+G_d) of a second cache), kv_len = R + G_d, bottom-right causal mask
+    Ks = torch.zeros((B, H, w.R + w.G_d, d), dtype=torch.bfloat16, device=DEV)
+    Vs = torch.zeros_like(Ks)
+    Ks[:, :, :w.R], Vs[:, :, :w.R] = Kr, Vr
+    tf.tf_kv_append(K[:, :, N - w.G_d:].contiguous(), V[:, :, N - w.G_d:].contiguous(), Ks, Vs, pos_all=w.R)
+    O_s = torch.empty(Qd.shape, dtype=torch.float32, device=DEV)
+    L_s = torch.empty(Qd.shape[:3], dtype=torch.float32, device=DEV)
+    tf.tf_decode_attn_retrieval(Qd, Ks, Vs, O_s, L_s, kv_len_all=w.R + w.G_d, causal=True)
     torch.cuda.synchronize()
     say(f"[{name}] device path done")
 
@@ -112,6 +121,14 @@ def test_one_layer_at_full_size(name, layer):
     eld = float(np.max(np.abs(L_d.cpu().numpy() - Ld)[same]))
     say(f"[{name}] draft attention on {int(same.sum())} units: max|dO|={ed:.2e} max|dLSE|={eld:.2e}")
     assert same.sum() >= 0.9 * B * H and ed <= ATTN_TOL and eld <= LSE_TOL
+    # the staged, causal draft pass, every unit: the draft cache written out from the device's own (valid)
+    # selection -- chunks in that order, then the newest G_d rows -- and plain attention over it
+    Os, Ls = oracle.attention_indexed(np.ascontiguousarray(Qu[:, :, -w.G_d:, :]), Ku, Vu, idx_h, w.c,
+                                      recent_begin=N - w.G_d, scale=1.0, causal=True)[:2]
+    es = float(np.max(np.abs(O_s.cpu().numpy() - Os)))
+    els = float(np.max(np.abs(L_s.cpu().numpy() - Ls)))
+    say(f"[{name}] staged causal draft attention, all units: max|dO|={es:.2e} max|dLSE|={els:.2e}")
+    assert es <= ATTN_TOL and els <= LSE_TOL
 
 
 @pytest.mark.parametrize("gamma", [2, 4, 6])
