@@ -100,9 +100,10 @@ def topk_case(rng, i):
     N = M * c + int(rng.integers(0, c))
     k = int(rng.integers(1, min(M, 300) + 1))
     bf = bool(rng.integers(0, 2))
+    fused = int(rng.choice([0, 1, 2]))                 # launch shape of the rebuild: automatic, fused, three kernels
     nc = [int(rng.integers(0, M + 1)) for _ in range(B)]
     nc[int(rng.integers(0, B))] = M
-    print(f"[{i}] topk B={B} H={H} c={c} M={M} N={N} k={k} bf16={bf} nc={nc}", flush=True)
+    print(f"[{i}] topk B={B} H={H} c={c} M={M} N={N} k={k} bf16={bf} fused={fused} nc={nc}", flush=True)
     x = synth.make_layer(B=B, H=H, N=N, G=2, c=c, P=min(4, M), seed=int(rng.integers(1 << 30)), device="cpu")
     K, V, q_r = x["K"].to(DEV), x["V"].to(DEV), x["q_r"].to(DEV)
     Kmean = torch.empty((B, H, M, 128), dtype=torch.bfloat16 if bf else torch.float32, device=DEV)
@@ -110,8 +111,12 @@ def topk_case(rng, i):
     idx = torch.empty((B, H, k), dtype=torch.int32, device=DEV)
     Kr = torch.zeros((B, H, k * c, 128), dtype=torch.bfloat16, device=DEV)
     Vr = torch.zeros_like(Kr)
-    (tf.tf_chunk_topk_gather_bf16 if bf else tf.tf_chunk_topk_gather)(q_r, Kmean, K, V, c, k, idx, Kr, Vr, n_chunks=torch.tensor(nc, dtype=torch.int32, device=DEV), n_chunks_all=M)
-    torch.cuda.synchronize()
+    tf.tf_set_thread_option("rebuild_fused", fused)
+    try:
+        (tf.tf_chunk_topk_gather_bf16 if bf else tf.tf_chunk_topk_gather)(q_r, Kmean, K, V, c, k, idx, Kr, Vr, n_chunks=torch.tensor(nc, dtype=torch.int32, device=DEV), n_chunks_all=M)
+        torch.cuda.synchronize()
+    finally:
+        tf.tf_set_thread_option("rebuild_fused", -1)
     if bf:
         km = oracle.chunk_mean_bf16(u16(x["K"]), c)        # the oracle's table; the device's must equal it bit for bit
         assert np.array_equal(u16_f64(u16(Kmean)), km)
