@@ -24,6 +24,9 @@
  *   tf_chunk_summarize_bf16, tf_chunk_topk_gather_bf16
  * and the accept step for batches with different draft lengths per sequence:
  *   tf_spec_accept_ragged
+ * and, for callers and measurement rather than for the method:
+ *   tf_decode_attn_retrieval_noalloc  the draft attention without a workspace argument
+ *   tf_set_option, tf_set_thread_option, tf_decode_attn_plan, tf_stream_read_probe
  *
  * Conventions (all calls)
  *   - Every data pointer is a DEVICE pointer owned by the caller (the only host pointers are

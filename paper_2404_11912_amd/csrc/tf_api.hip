@@ -32,7 +32,7 @@ int accept_launch(const float *, const float *, const int32_t *, int32_t, int32_
 
 extern "C" {
 
-int tf_version(void) { return 200; /* 0.2.0 */ }
+int tf_version(void) { return 300; /* 0.3.0 */ }
 
 const char *tf_status_string(int code) {
     switch (code) {
