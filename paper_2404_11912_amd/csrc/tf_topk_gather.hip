@@ -1,7 +1,7 @@
 // tf_chunk_topk_gather: retrieval-cache construction (Sec. 4.1 / Sec. 4.3): score every
 // chunk by query . average-key, keep the k best in descending order, gather their K/V.
 //
-// Three kernels on one stream:
+// Two launch shapes on one stream. Few (b,h) units in the call (one layer): three kernels,
 //   score   HBM streaming over the fp32 average-key table (512 B per chunk). A wave takes 16
 //           chunk rows at a time, 8 lanes per row reading whole 128-byte lines; 32 fp32 FMAs
 //           per lane against the resident query, three shuffles per row finish the dot product.
@@ -11,6 +11,9 @@
 //           (score desc, index asc) by counting the winners above it in LDS.
 //   gather  one wave per selected chunk copies its rows (256 B each) of K and V with 16-byte
 //           loads and stores.
+// Many units (all layers of a decode step in one call): score and select fused into one kernel,
+// one workgroup per unit, the unit's score keys held in LDS (score_select_kernel below), then the
+// same gather. Both shapes compute the same fp32 scores in the same order and return the same bits.
 #include <atomic>
 #include <type_traits>
 
