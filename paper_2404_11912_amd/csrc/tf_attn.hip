@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnParams p) {
     };
 
     // Q operand of the QK^T MFMAs, kept in LDS (re-read per tile: 4 KiB per tile is nothing for
-    // LDS, and 16 VGPRs fewer per lane buy a third wave per SIMD): entry [kk][lane] holds
+    // LDS, and the lane has 16 VGPRs more for loads in flight): entry [kk][lane] holds
     // Q[query r][32kk + 8s .. +8] for lane (r,s), zero for r >= G
     // Every wave keeps a copy of its own: a lane reads back only what it wrote itself, so no
     // barrier stands between the start of the kernel and the first K/V loads.
@@ -818,8 +818,8 @@ size_t attn_noalloc_max_bytes() { return kScratchBytes; }
 int attn_retrieval_noalloc_launch(const void *Q, const void *K, const void *V, const tf_kv_desc *kd,
                                   const int32_t *kv_len, int64_t kv_len_all, int32_t G, float scale, int32_t causal,
                                   float *O, float *LSE, void *stream) {
-    // the size check comes first and touches no device: a too-large problem is refused the same way
-    // whether or not the scratch address has been looked up yet
+    // the size check comes first (host arithmetic and a cached attribute query only): a too-large
+    // problem is refused the same way whether or not the scratch address has been looked up yet
     if (kd && kd->batch > 0 && kd->heads > 0 && kv_len_all > 0 && G > 0) {
         const int q_group = kd->q_group > 0 ? kd->q_group : 1;
         const int64_t BH = (int64_t)kd->batch * kd->heads;
