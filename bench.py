@@ -189,6 +189,12 @@ class Step:
         back to back -- (used outside the timed region for the breakdown)."""
         def call(name, fn, *args):
             if all_events is not None:
+                # breakdown only: two untimed verification-layer calls first (0.6 ms of real streaming),
+                # so that the host has queued the whole group before the GPU starts it and the pair
+                # measures device time (the 32 draft launches are about as long as the Python calls
+                # that enqueue them; an idle delay instead would let the memory clock drop)
+                for l in range(min(2, self.L)):
+                    self.verify_attn(l)
                 all_events.append((name, *_timed(lambda: fn(*args))))
             else:
                 fn(*args)
